@@ -6,15 +6,21 @@ tensors are already resident in HBM; the plan is built and uploaded once (the pa
 update) and its time is reported separately.  The KV pools are rotated over enough independent
 copies that no step finds its KV in the 256 MB last-level cache.
 
-Prints ONE JSON line: unique-KV bandwidth of the whole step as `value`, the forward kernel's
-roofline (HIP-event timed inside this run) as `roofline`, and the fp64 oracle timed on the host
-cores as `cpu_baseline`.
+One invocation runs the benchmark shapes C2, C3, C4 and C5 one after the other and prints ONE
+JSON line.  `value`, `ms_per_step`, `roofline` and `cpu_baseline` are those of the largest shape
+(C5); `per_config` carries the same measurements for every shape: step time (median and mean over
+several replays of a HIP graph of exactly `--steps` steps), forward and merge kernel times, unique
+KV bytes, the fraction of 8 TB/s and of a streaming-read ceiling measured in the same run by a
+plain 16-byte-load read kernel, the one-query-per-workgroup plan timed the same way, and the
+max-abs error against the fp64 oracle on a sample of requests.
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -22,118 +28,48 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+REPLAYS = 5
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="C2", help="C1..C5 (default C2: Llama-3-8B layer shape)")
-    ap.add_argument("--mode", default="pat", choices=["pat", "naive", "nosharing"])
-    ap.add_argument("--layout", default="NHD", choices=["NHD", "HND"])
-    ap.add_argument("--split", default="auto", help="auto | mean | none | <target tokens>")
-    ap.add_argument("--force-tile", type=int, default=-1)
-    ap.add_argument("--hot", action="store_true", help="single KV copy (cache-resident numbers)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--model", default="", help="run-time model of the split, four ns values a,b,c,d "
-                    "(python -m paper_2511_22333_amd.calibrate prints one)")
-    ap.add_argument("--profile", action="store_true",
-                    help="for rocprofv3 runs: eager launches only (no graphs, no baselines) and "
-                         "three plain 1 GiB device copies at the end as a counter calibration")
-    ap.add_argument("--no-baseline-mode", action="store_true",
-                    help="skip timing the one-query-per-workgroup plan")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU; the path shards by KV head or by prefix "
-            "subtree without any exchange, which is not built here. Use --gpus 1.")
-        sys.exit(2)
+def git_head():
+    try:
+        return subprocess.check_output(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"],
+                                       stderr=subprocess.DEVNULL).decode().strip()
+    except Exception:
+        return None
 
-    import numpy as np
-    import torch
-    from paper_2511_22333_amd import binding as pb
-    from paper_2511_22333_amd import workloads as wl
 
-    if not torch.cuda.is_available():
-        log("bench.py: no GPU visible")
-        sys.exit(1)
-    torch.cuda.set_device(0)
-    batch = wl.config(args.config)
-    mode = {"pat": pb.PAT_MODE_PAT, "naive": pb.PAT_MODE_NAIVE_PER_NODE,
-            "nosharing": pb.PAT_MODE_NO_SHARING}[args.mode]
-    kw = dict(mode=mode, force_tile=args.force_tile)
-    if args.split == "auto":
-        kw["split_policy"] = pb.PAT_SPLIT_AUTO
-    elif args.split == "mean":
-        kw["split_policy"] = pb.PAT_SPLIT_MEAN
-    elif args.split == "none":
-        kw["split_policy"] = pb.PAT_SPLIT_NONE
-    else:
-        kw["split_policy"] = pb.PAT_SPLIT_TARGET
-        kw["split_target_tokens"] = int(args.split)
+def stored_traffic(config, mode, stats, unique_bytes):
+    """HBM traffic of the forward kernel from the committed rocprofv3 counter runs (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy).  Not measured
+    in this run: tagged with where it comes from, and dropped when it was taken on another plan."""
+    path = os.path.join(ROOT, "profiles", "forward_traffic.json")
+    try:
+        entry = json.load(open(path)).get(f"{config}:{mode}")
+    except Exception:
+        return None
+    if not entry:
+        return None
+    if entry.get("unique_kv_bytes", unique_bytes) != unique_bytes or \
+            entry.get("workgroups", int(stats.num_workgroups)) != int(stats.num_workgroups):
+        return None
+    entry = dict(entry)
+    entry["source"] = "profiles/forward_traffic.json (rocprofv3 --pmc runs, not this run)"
+    return entry
 
-    if args.model:
-        kw["model_ns"] = [int(x) for x in args.model.split(",")]
 
-    # ---- plan (timed on the host, not part of a step) ----
-    t0 = time.perf_counter()
-    plan = pb.plan_for_batch(batch, **kw)
-    plan_us = (time.perf_counter() - t0) * 1e6
-    st = plan.stats()
-    dev, ws = pb.alloc_plan_buffers(plan)
-    pb.pat_plan_upload(plan, dev)
-    # lazy update on a second plan of the same batch: 16 decode steps, every request one token
-    # longer per step (so every request crosses one page boundary), host time per step
-    import dataclasses
-    roomy = dataclasses.replace(batch, num_pages=batch.num_pages + 2 * batch.num_requests)
-    lazy = pb.plan_for_batch(roomy, **kw)
-    grown, adv = roomy, []
-    for _ in range(16):
-        grown = wl.decode_steps(grown, 1)
-        t0 = time.perf_counter()
-        pb.pat_plan_advance(lazy, grown.kv_lens, grown.block_tables)
-        adv.append((time.perf_counter() - t0) * 1e6)
-    advance_us = float(np.median(adv))
-    del lazy
-    unique_bytes = int(st.unique_kv_tokens) * batch.bytes_per_token()
-    log(f"[bench] {args.config} mode={args.mode} B={batch.num_requests} items={st.num_items} "
-        f"workgroups={st.num_workgroups} slots={st.num_slots} unique_kv={unique_bytes / 1e6:.1f} MB "
-        f"total_kv={st.total_kv_tokens * batch.bytes_per_token() / 1e6:.1f} MB plan={plan_us:.0f} us "
-        f"advance={advance_us:.1f} us/step "
-        f"tiles={list(st.tile_histogram)[:pb.lib.pat_num_tiles()]}")
+class Timer:
+    """HIP graphs of back-to-back launches, replayed and timed with HIP events on their stream."""
 
-    # ---- tensors: R rotated copies of the KV pools ----
-    pool_bytes = 2 * batch.num_pages * batch.page_size * batch.num_kv_heads * batch.head_dim * 2
-    if args.hot:
-        R = 1
-    else:
-        R = max(1, min(64, -(-(1 << 30) // max(1, unique_bytes))))
-        if unique_bytes >= (1 << 30):
-            R = 2 if pool_bytes * 2 < (64 << 30) else 1
-    copies = []
-    for i in range(R):
-        q, kp, vp, strides = wl.make_tensors(batch, seed=batch.seed + i, device="cuda",
-                                             layout=args.layout)
-        copies.append((q, kp, vp))
-    out = torch.empty_like(copies[0][0])
-    lse = torch.empty(batch.num_requests, batch.num_q_heads, dtype=torch.float32, device="cuda")
-    scale = batch.softmax_scale
-    log(f"[bench] {R} KV copies x {pool_bytes / 1e6:.0f} MB")
+    def __init__(self, torch):
+        self.torch = torch
 
-    def step(i):
-        q, kp, vp = copies[i % R]
-        pb.pat_decode_attention(plan, q, kp, vp, strides, scale, out, lse, ws)
-
-    def fwd(i):
-        q, kp, vp = copies[i % R]
-        pb.pat_forward(plan, q, kp, vp, strides, scale, out, lse, ws)
-
-    def capture(fn, n):
-        """n consecutive launches of fn as one HIP graph (no CPU launch cost on replay)."""
+    def capture(self, fn, n):
+        torch = self.torch
         g = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -146,8 +82,17 @@ def main():
                 fn(i)
         return g
 
-    def timed_replay(g, n):
-        """One replay bracketed by HIP events on the stream it runs on; us per launch."""
+    def replay_us(self, g, n):
+        """One replay; us per launch, wall clock between two synchronisations."""
+        torch = self.torch
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e6
+
+    def replay_event_us(self, g, n):
+        torch = self.torch
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         a.record()
@@ -155,6 +100,111 @@ def main():
         b.record()
         torch.cuda.synchronize()
         return a.elapsed_time(b) * 1e3 / n
+
+    def stats(self, g, n, how="wall"):
+        fn = self.replay_us if how == "wall" else self.replay_event_us
+        fn(g, n)                                    # warm-up replay
+        runs = sorted(fn(g, n) for _ in range(REPLAYS))
+        return {"median": runs[len(runs) // 2], "mean": sum(runs) / len(runs),
+                "min": runs[0], "max": runs[-1]}
+
+
+def oracle_sample(np, torch, batch, tensors, strides, ids):
+    """fp64 oracle over the listed requests (their pages gathered from the GPU pools)."""
+    from oracle import attention as oa
+    q, kp, vp = tensors
+    P = batch.page_size
+    pages = np.unique(np.concatenate(
+        [batch.block_tables[r, : -(-int(batch.kv_lens[r]) // P)] for r in ids]))
+    remap = np.full(batch.num_pages, -1, np.int64)
+    remap[pages] = np.arange(len(pages))
+    idx = torch.from_numpy(pages.astype(np.int64)).cuda()
+    kc, vc, qc = kp[idx].cpu(), vp[idx].cpu(), q.cpu()
+    bt = np.where(batch.block_tables >= 0, remap[np.maximum(batch.block_tables, 0)], -1)
+    t0 = time.perf_counter()
+    o_ref, l_ref = oa.decode_attention(qc, kc, vc, bt.astype(np.int32), batch.kv_lens,
+                                       page_size=P, num_kv_heads=batch.num_kv_heads,
+                                       dtype=batch.dtype, scale=batch.softmax_scale,
+                                       strides=strides, num_pages=len(pages), req_ids=ids)
+    return o_ref, l_ref, time.perf_counter() - t0, oa.num_threads()
+
+
+def run_config(name, args, ceiling_gbps, headline):
+    """Everything measured on one workload; returns a dict."""
+    import numpy as np
+    import torch
+    from paper_2511_22333_amd import binding as pb
+    from paper_2511_22333_amd import workloads as wl
+
+    batch = wl.config(name)
+    mode = {"pat": pb.PAT_MODE_PAT, "naive": pb.PAT_MODE_NAIVE_PER_NODE,
+            "nosharing": pb.PAT_MODE_NO_SHARING}[args.mode]
+    kw = dict(mode=mode, force_tile=args.force_tile)
+    if args.split == "auto":
+        kw["split_policy"] = pb.PAT_SPLIT_AUTO
+    elif args.split == "mean":
+        kw["split_policy"] = pb.PAT_SPLIT_MEAN
+    elif args.split == "none":
+        kw["split_policy"] = pb.PAT_SPLIT_NONE
+    else:
+        kw["split_policy"] = pb.PAT_SPLIT_TARGET
+        kw["split_target_tokens"] = int(args.split)
+    if args.model:
+        kw["model_ns"] = [int(x) for x in args.model.split(",")]
+
+    # ---- plan (timed on the host, not part of a step) ----
+    t0 = time.perf_counter()
+    plan = pb.plan_for_batch(batch, **kw)
+    plan_us = (time.perf_counter() - t0) * 1e6
+    st = plan.stats()
+    dev, ws = pb.alloc_plan_buffers(plan)
+    pb.pat_plan_upload(plan, dev)
+    # lazy update on a second plan of the same batch: 16 decode steps, every request one token
+    # longer per step (so every request crosses one page boundary), host time per step
+    roomy = dataclasses.replace(batch, num_pages=batch.num_pages + 2 * batch.num_requests)
+    lazy = pb.plan_for_batch(roomy, **kw)
+    grown, adv = roomy, []
+    for _ in range(16):
+        grown = wl.decode_steps(grown, 1)
+        t0 = time.perf_counter()
+        pb.pat_plan_advance(lazy, grown.kv_lens, grown.block_tables)
+        adv.append((time.perf_counter() - t0) * 1e6)
+    advance_us = float(np.median(adv))
+    del lazy
+    unique_bytes = int(st.unique_kv_tokens) * batch.bytes_per_token()
+    total_bytes = int(st.total_kv_tokens) * batch.bytes_per_token()
+    n_tiles = pb.lib.pat_num_tiles()
+    log(f"[bench] {name} mode={args.mode} B={batch.num_requests} items={st.num_items} "
+        f"workgroups={st.num_workgroups} slots={st.num_slots} unique_kv={unique_bytes / 1e6:.1f} MB "
+        f"total_kv={total_bytes / 1e6:.1f} MB plan={plan_us:.0f} us advance={advance_us:.1f} us/step "
+        f"tiles={list(st.tile_histogram)[:n_tiles]}")
+
+    # ---- tensors: R rotated copies of the KV pools ----
+    pool_bytes = 2 * batch.num_pages * batch.page_size * batch.num_kv_heads * batch.head_dim * 2
+    if args.hot:
+        R = 1
+    else:
+        R = max(1, min(64, -(-(1 << 30) // max(1, unique_bytes))))
+        if unique_bytes >= (1 << 30):
+            R = 2 if pool_bytes * 2 < (64 << 30) else 1
+    copies = []
+    strides = None
+    for i in range(R):
+        q, kp, vp, strides = wl.make_tensors(batch, seed=batch.seed + i, device="cuda",
+                                             layout=args.layout)
+        copies.append((q, kp, vp))
+    out = torch.empty_like(copies[0][0])
+    lse = torch.empty(batch.num_requests, batch.num_q_heads, dtype=torch.float32, device="cuda")
+    scale = batch.softmax_scale
+    log(f"[bench] {name}: {R} KV copies x {pool_bytes / 1e6:.0f} MB")
+
+    def step(i):
+        q, kp, vp = copies[i % R]
+        pb.pat_decode_attention(plan, q, kp, vp, strides, scale, out, lse, ws)
+
+    def fwd(i):
+        q, kp, vp = copies[i % R]
+        pb.pat_forward(plan, q, kp, vp, strides, scale, out, lse, ws)
 
     # ---- eager launches from Python (includes the CPU's launch cost) ----
     for i in range(args.warmup):
@@ -175,56 +225,47 @@ def main():
         for _ in range(3):
             dst.copy_(src)                          # plain copy kernel: 1 GiB read, 1 GiB written
         torch.cuda.synchronize()
-        print(json.dumps({"profile_run": True, "config": args.config, "mode": args.mode,
-                          "steps": args.steps, "eager_us_per_step": round(eager_us, 2),
-                          "unique_kv_bytes": unique_bytes, "workgroups": int(st.num_workgroups),
-                          "copy_calibration_bytes": 1 << 30}), flush=True)
-        return
+        return {"profile_run": True, "config": name, "mode": args.mode, "steps": args.steps,
+                "eager_us_per_step": round(eager_us, 2), "unique_kv_bytes": unique_bytes,
+                "workgroups": int(st.num_workgroups), "copy_calibration_bytes": 1 << 30}
 
-    # ---- the timed region: exactly `steps` steps, launched as one HIP graph ----
-    g_step = capture(step, args.steps)
-    g_step.replay()                                 # warm-up replay
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    g_step.replay()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    us_per_step = wall / args.steps * 1e6
-    gbps = unique_bytes / (wall / args.steps) / 1e9
+    # ---- the timed region: a HIP graph of exactly `steps` steps, replayed REPLAYS times ----
+    tm = Timer(torch)
+    g_step = tm.capture(step, args.steps)
+    step_us = tm.stats(g_step, args.steps, "wall")
+    del g_step
+    gbps = unique_bytes / (step_us["median"] * 1e-6) / 1e9
 
     # ---- per-kernel durations: HIP events around graphs of back-to-back launches ----
     n_ev = max(R, min(args.steps, 100))
-    g_fwd = capture(fwd, n_ev)
-    g_mrg = capture(lambda i: pb.pat_merge(plan, out, lse, ws), n_ev)
-    timed_replay(g_fwd, n_ev)
-    fwd_runs = sorted(timed_replay(g_fwd, n_ev) for _ in range(5))
-    mrg_runs = sorted(timed_replay(g_mrg, n_ev) for _ in range(5))
-    fwd_mean_us, fwd_med_us = sum(fwd_runs) / len(fwd_runs), fwd_runs[len(fwd_runs) // 2]
-    mrg_mean_us, mrg_med_us = sum(mrg_runs) / len(mrg_runs), mrg_runs[len(mrg_runs) // 2]
-    log(f"[bench] step {us_per_step:.1f} us as a graph ({gbps:.0f} GB/s unique KV), "
-        f"{eager_us:.1f} us launched eagerly from Python; kernels back to back: "
-        f"fwd {fwd_med_us:.1f} merge {mrg_med_us:.1f} us")
+    g_fwd = tm.capture(fwd, n_ev)
+    fwd_us = tm.stats(g_fwd, n_ev, "event")
+    del g_fwd
+    if int(st.num_merge_requests) > 0:
+        g_mrg = tm.capture(lambda i: pb.pat_merge(plan, out, lse, ws), n_ev)
+        mrg_us = tm.stats(g_mrg, n_ev, "event")
+        del g_mrg
+    else:
+        mrg_us = {"median": 0.0, "mean": 0.0, "min": 0.0, "max": 0.0}
+    log(f"[bench] {name}: step {step_us['median']:.1f} us median / {step_us['mean']:.1f} mean as a graph "
+        f"({gbps:.0f} GB/s unique KV), {eager_us:.1f} us launched eagerly from Python; kernels back "
+        f"to back: fwd {fwd_us['median']:.1f} merge {mrg_us['median']:.1f} us")
 
     # algorithmic bytes of one forward launch: every unique KV byte once
-    fwd_bytes = unique_bytes
     algo_total = (unique_bytes + 2 * batch.num_requests * batch.num_q_heads * batch.head_dim * 2
                   + batch.num_requests * batch.num_q_heads * 4
                   + 2 * int(st.num_slots) * batch.num_q_heads * (batch.head_dim + 1) * 4)
-    achieved = fwd_bytes / (fwd_mean_us * 1e-6) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "forward_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(f"{args.config}:{args.mode}")
-        except Exception:
-            traffic = None
+    achieved = unique_bytes / (fwd_us["mean"] * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                "kernel": "forward", "kernel_us_mean": round(fwd_mean_us, 2),
-                "kernel_us_median": round(fwd_med_us, 2), "merge_us_median": round(mrg_med_us, 2),
-                "algorithmic_bytes": fwd_bytes, "algorithmic_bytes_with_qo_partials": algo_total}
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": stored_traffic(name, args.mode, st, unique_bytes),
+                "kernel": "forward", "kernel_us_mean": round(fwd_us["mean"], 2),
+                "kernel_us_median": round(fwd_us["median"], 2),
+                "merge_us_median": round(mrg_us["median"], 2),
+                "frac_of_read_ceiling": round(achieved / ceiling_gbps, 4) if ceiling_gbps else None,
+                "algorithmic_bytes": unique_bytes, "algorithmic_bytes_with_qo_partials": algo_total}
 
-    # ---- one-query-per-workgroup plan through the same kernels ----
+    # ---- one-query-per-workgroup plan through the same kernels, timed the same way ----
     baseline_mode = None
     if not args.no_baseline_mode and args.mode == "pat":
         kw2 = dict(kw)
@@ -237,77 +278,167 @@ def main():
             q, kp, vp = copies[i % R]
             pb.pat_decode_attention(plan2, q, kp, vp, strides, scale, out, lse, ws2)
 
-        n2 = max(5, min(args.steps, 50))
-        for i in range(3):
-            step2(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(n2):
-            step2(i)
-        torch.cuda.synchronize()
-        us2 = (time.perf_counter() - t0) / n2 * 1e6
-        baseline_mode = {"mode": "one-query-per-workgroup plan, same kernels",
-                         "us_per_step": round(us2, 2), "speedup": round(us2 / us_per_step, 3),
+        g2 = tm.capture(step2, args.steps)
+        us2 = tm.stats(g2, args.steps, "wall")
+        del g2
+        baseline_mode = {"mode": "one-query-per-workgroup plan, same kernels, same graph timing",
+                         "us_per_step": round(us2["median"], 2),
+                         "speedup": round(us2["median"] / step_us["median"], 3),
                          "sharing_ratio": round(st.total_kv_tokens / st.unique_kv_tokens, 3)}
-        log(f"[bench] no-sharing plan: {us2:.1f} us/step -> speed-up {us2 / us_per_step:.2f}x")
+        log(f"[bench] {name}: no-sharing plan {us2['median']:.1f} us/step -> speed-up "
+            f"{us2['median'] / step_us['median']:.2f}x")
+        del plan2, dev2, ws2
 
-    # ---- fp64 oracle on the host cores (bounded sample) ----
-    cpu_baseline = None
+    # ---- fp64 oracle on the host cores ----
+    # headline: a bounded sample of ~10-30 s (requests in index order until ~6e9 multiply-adds),
+    # timed, as the CPU baseline; the other shapes: eight requests, for the error only
+    cpu_baseline, max_err = None, None
     if not args.no_cpu_baseline:
-        from oracle import attention as oa
-        q, kp, vp = copies[0]
         lens = batch.kv_lens.astype(np.int64)
-        # about 10-30 s of oracle work: requests in index order until ~6e9 multiply-adds
-        budget = 6e9
-        cost = np.cumsum(lens * batch.num_q_heads * batch.head_dim * 2)
-        n_req = int(max(1, min(batch.num_requests, np.searchsorted(cost, budget) + 1)))
-        ids = list(range(n_req))
-        pages = np.unique(np.concatenate(
-            [batch.block_tables[r, : -(-int(lens[r]) // batch.page_size)] for r in ids]))
-        remap = np.full(batch.num_pages, -1, np.int64)
-        remap[pages] = np.arange(len(pages))
-        idx = torch.from_numpy(pages.astype(np.int64)).cuda()
-        kc, vc, qc = kp[idx].cpu(), vp[idx].cpu(), q.cpu()
-        bt = np.where(batch.block_tables >= 0, remap[np.maximum(batch.block_tables, 0)], -1)
-        t0 = time.perf_counter()
-        o_ref, l_ref = oa.decode_attention(qc, kc, vc, bt.astype(np.int32), batch.kv_lens,
-                                           page_size=batch.page_size,
-                                           num_kv_heads=batch.num_kv_heads, dtype=batch.dtype,
-                                           scale=scale, strides=strides, num_pages=len(pages),
-                                           req_ids=ids)
-        cpu_s = time.perf_counter() - t0
-        # the sample's share of the step, in the metric's unit: bytes the oracle walked per second
-        sample_tokens = int(lens[:n_req].sum())
-        cpu_gbps = sample_tokens * batch.bytes_per_token() / cpu_s / 1e9
+        if headline:
+            cost = np.cumsum(lens * batch.num_q_heads * batch.head_dim * 2)
+            n_req = int(max(1, min(batch.num_requests, np.searchsorted(cost, 6e9) + 1)))
+            ids = list(range(n_req))
+        else:
+            rng = np.random.default_rng(5)
+            ids = sorted({int(np.argmax(lens)), int(np.argmin(lens)),
+                          *[int(x) for x in rng.choice(batch.num_requests, 6, replace=False)]})
+        o_ref, l_ref, cpu_s, threads = oracle_sample(np, torch, batch, copies[0], strides, ids)
         step(0)                                   # copy 0 -> compare the same requests
         torch.cuda.synchronize()
-        err = float(np.abs(out[:n_req].double().cpu().numpy() - o_ref).max())
-        cpu_baseline = {"value": round(cpu_gbps, 4), "unit": "GB/s", "cores": oa.num_threads(),
-                        "kind": "oracle",
-                        "sample": f"requests 0..{n_req - 1} of {batch.num_requests} "
-                                  f"({sample_tokens} KV tokens attended, one request at a time, "
-                                  f"fp64, {cpu_s:.2f} s)",
-                        "seconds": round(cpu_s, 3), "max_abs_err_vs_gpu": err}
-        log(f"[bench] oracle: {cpu_s:.2f} s on {oa.num_threads()} threads for {n_req} requests; "
-            f"max-abs err vs GPU {err:.2e}")
+        max_err = float(np.abs(out[ids].double().cpu().numpy() - o_ref).max())
+        lse_err = float(np.abs(lse[ids].double().cpu().numpy() - l_ref).max())
+        sample_tokens = int(lens[ids].sum())
+        log(f"[bench] {name}: oracle {cpu_s:.2f} s on {threads} threads for {len(ids)} requests; "
+            f"max-abs err vs GPU {max_err:.2e} (lse {lse_err:.2e})")
+        if headline:
+            cpu_gbps = sample_tokens * batch.bytes_per_token() / cpu_s / 1e9
+            cpu_baseline = {"value": round(cpu_gbps, 4), "unit": "GB/s", "cores": threads,
+                            "kind": "oracle",
+                            "sample": f"requests 0..{len(ids) - 1} of {batch.num_requests} "
+                                      f"({sample_tokens} KV tokens attended, one request at a time, "
+                                      f"fp64, {cpu_s:.2f} s)",
+                            "seconds": round(cpu_s, 3), "max_abs_err_vs_gpu": max_err}
 
-    result = {
-        "metric": "decode_attention_unique_kv_bandwidth", "value": round(gbps, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(us_per_step / 1e3, 6), "us_per_step": round(us_per_step, 2),
+    res = {
+        "workload": name,
+        "description": f"B={batch.num_requests}, Hq/Hkv={batch.num_q_heads}/{batch.num_kv_heads}, "
+                       f"d=128, page 16, {batch.dtype}, layout {args.layout}",
+        "dtype": batch.dtype, "mode": args.mode, "kv_copies_rotated": R,
+        "unique_kv_bytes": unique_bytes, "total_kv_bytes_one_query_per_wg": total_bytes,
+        "items": int(st.num_items), "workgroups": int(st.num_workgroups),
+        "partial_slots": int(st.num_slots),
+        "tile_histogram": list(st.tile_histogram)[:n_tiles],
+        "plan_us": round(plan_us, 1), "plan_advance_us_per_decode_step": round(advance_us, 1),
+        "steps_per_replay": args.steps, "replays": REPLAYS,
+        "step_us_median": round(step_us["median"], 2), "step_us_mean": round(step_us["mean"], 2),
+        "step_us_min": round(step_us["min"], 2), "step_us_max": round(step_us["max"], 2),
         "eager_us_per_step": round(eager_us, 2),
+        "forward_us_median": round(fwd_us["median"], 2), "forward_us_mean": round(fwd_us["mean"], 2),
+        "merge_us_median": round(mrg_us["median"], 2), "merge_us_mean": round(mrg_us["mean"], 2),
+        "step_gbps": round(gbps, 1), "step_frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+        "step_frac_of_read_ceiling": round(gbps / ceiling_gbps, 4) if ceiling_gbps else None,
+        "forward_frac_of_hbm_peak": roofline["frac"],
+        "forward_frac_of_read_ceiling": roofline["frac_of_read_ceiling"],
+        "no_sharing_plan": baseline_mode,
+        "max_abs_err_vs_oracle_on_sample": max_err,
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    del copies, out, lse, plan, dev, ws
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--configs", default="C2,C3,C4,C5",
+                    help="workloads to run, in order; the largest one is the headline")
+    ap.add_argument("--config", default="", help="one workload only (C1..C5, T3, H32, H16, PK)")
+    ap.add_argument("--mode", default="pat", choices=["pat", "naive", "nosharing"])
+    ap.add_argument("--layout", default="NHD", choices=["NHD", "HND"])
+    ap.add_argument("--split", default="auto", help="auto | mean | none | <target tokens>")
+    ap.add_argument("--force-tile", type=int, default=-1)
+    ap.add_argument("--hot", action="store_true", help="single KV copy (cache-resident numbers)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--model", default="", help="run-time model of the split, four ns values a,b,c,d "
+                    "(python -m paper_2511_22333_amd.calibrate prints one)")
+    ap.add_argument("--profile", action="store_true",
+                    help="for rocprofv3 runs: eager launches only (no graphs, no baselines) and "
+                         "three plain 1 GiB device copies at the end as a counter calibration")
+    ap.add_argument("--no-baseline-mode", action="store_true",
+                    help="skip timing the one-query-per-workgroup plan")
+    ap.add_argument("--no-read-ceiling", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; the path shards by KV head or by prefix "
+            "subtree without any exchange, which is not built here. Use --gpus 1.")
+        sys.exit(2)
+
+    import torch
+    from paper_2511_22333_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    names = [args.config] if args.config else [x for x in args.configs.split(",") if x]
+
+    # ---- streaming-read ceiling of this GPU, this run: plain 16-byte loads over 4 GiB ----
+    ceiling = None
+    if not args.no_read_ceiling and not args.profile:
+        from paper_2511_22333_amd import probe
+        buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda")
+        buf.fill_(1)
+        plain, nt = probe.read_ceiling(buf)
+        del buf
+        torch.cuda.empty_cache()
+        ceiling = {"bytes": 4 << 30, "plain_16B_loads_gbps": round(plain, 1),
+                   "nontemporal_16B_loads_gbps": round(nt, 1), "gbps": round(max(plain, nt), 1),
+                   "frac_of_hbm_peak": round(max(plain, nt) / HBM_PEAK_GBPS, 4)}
+        log(f"[bench] read ceiling over 4 GiB: {plain:.0f} GB/s plain, {nt:.0f} GB/s non-temporal")
+    ceiling_gbps = ceiling["gbps"] if ceiling else None
+
+    # headline = the largest workload (most unique KV bytes)
+    sizes = {n: wl.config(n).unique_kv_bytes() for n in names} if len(names) > 1 else {names[0]: 0}
+    head_name = max(names, key=lambda n: sizes[n])
+    results = []
+    for n in names:
+        results.append(run_config(n, args, ceiling_gbps, headline=(n == head_name)))
+    if args.profile:
+        print(json.dumps(results[0]), flush=True)
+        return
+    head = next(r for r in results if r["workload"] == head_name)
+    per_config = []
+    for r in results:
+        r = dict(r)
+        r.pop("cpu_baseline")
+        rf = r.pop("roofline")
+        r["traffic"] = rf["traffic"]
+        per_config.append(r)
+    result = {
+        "metric": "decode_attention_unique_kv_bandwidth", "value": head["step_gbps"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(head["step_us_median"] / 1e3, 6), "us_per_step": head["step_us_median"],
+        "us_per_step_mean": head["step_us_mean"], "replays": REPLAYS,
+        "eager_us_per_step": head["eager_us_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": batch.dtype, "data": "synthetic",
-        "config": {"workload": f"{args.config}: B={batch.num_requests}, Hq/Hkv="
-                               f"{batch.num_q_heads}/{batch.num_kv_heads}, d=128, page 16, "
-                               f"{batch.dtype}, layout {args.layout}",
-                   "mode": args.mode, "kv_copies_rotated": R, "launch": "hip_graph",
-                   "unique_kv_bytes": unique_bytes,
-                   "total_kv_bytes_one_query_per_wg": int(st.total_kv_tokens) * batch.bytes_per_token(),
-                   "items": int(st.num_items), "workgroups": int(st.num_workgroups),
-                   "plan_us": round(plan_us, 1), "plan_advance_us_per_decode_step": round(advance_us, 1)},
-        "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "no_sharing_plan": baseline_mode,
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": f"{head['workload']}: {head['description']}",
+                   "mode": args.mode, "kv_copies_rotated": head["kv_copies_rotated"],
+                   "launch": "hip_graph", "unique_kv_bytes": head["unique_kv_bytes"],
+                   "total_kv_bytes_one_query_per_wg": head["total_kv_bytes_one_query_per_wg"],
+                   "items": head["items"], "workgroups": head["workgroups"],
+                   "plan_us": head["plan_us"],
+                   "plan_advance_us_per_decode_step": head["plan_advance_us_per_decode_step"]},
+        "frac_of_hbm_peak": head["step_frac_of_hbm_peak"],
+        "frac_of_read_ceiling": head["step_frac_of_read_ceiling"],
+        "read_ceiling": ceiling,
+        "roofline": head["roofline"], "cpu_baseline": head["cpu_baseline"],
+        "no_sharing_plan": head["no_sharing_plan"],
+        "per_config": per_config, "head": git_head(),
     }
     print(json.dumps(result), flush=True)
 

@@ -213,6 +213,7 @@ int pat_tile_info(int tile_id, int *m, int *n);
  *   k_pool     device; element (page, token, kv head, c) at
  *   v_pool       page*kv_stride_page + token*kv_stride_token + head*kv_stride_head + c
  *              (strides in elements; d contiguous; 16-byte aligned rows)
+ *   softmax_scale  finite and > 0, else PAT_ERR_INVALID_ARG
  *   out        device [B][Hq][d], dtype
  *   lse        device [B][Hq] fp32, natural log of sum exp(scaled scores); may be NULL
  *   workspace  device, >= stats.workspace_bytes, 256-byte aligned                              */

@@ -10,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libpat.so")
+PROBE_LIB = os.path.join(HERE, "libpat_probe.so")       # measurement kernels (bench, calibration)
 
 SOURCES = ["pat_plan.cpp", "pat_api.hip", "pat_forward.hip", "pat_merge.hip"]
 
@@ -53,6 +54,12 @@ def build(verbose: bool = False, jobs: int = 4) -> str:
     if verbose:
         print(" ".join(link), flush=True)
     subprocess.check_call(link)
+    probe = [hipcc(), *HIP_FLAGS, "-shared", "-o", PROBE_LIB, os.path.join(CSRC, "pat_probe.hip")]
+    if verbose:
+        print(" ".join(probe), flush=True)
+    out = subprocess.run(probe, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+    if out.returncode != 0:
+        raise RuntimeError("hipcc failed on pat_probe.hip:\n" + out.stdout.decode(errors="replace"))
     return LIB
 
 

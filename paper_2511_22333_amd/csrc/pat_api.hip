@@ -1,6 +1,7 @@
 // C ABI of libpat.so: argument checks, plan lifetime, upload, and kernel launches.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstring>
 #include <memory>
 #include <new>
@@ -215,6 +216,8 @@ int pat_forward(const pat_plan_t *plan, const void *q, const void *k_pool, const
                 float softmax_scale, void *out, float *lse, void *workspace,
                 size_t workspace_bytes, void *stream)
 {
+    // the packed tiles take the row maximum before scaling: the scale must keep the order
+    if (!std::isfinite(softmax_scale) || !(softmax_scale > 0.f)) return PAT_ERR_INVALID_ARG;
     int rc = check_ws(plan, workspace, workspace_bytes);
     if (rc != PAT_OK) return rc;
     if (!q || !k_pool || !v_pool || !out) return PAT_ERR_INVALID_ARG;

@@ -121,18 +121,15 @@ hipError_t launch_forward(int dtype, const FwdArgs &a, int n_workgroups, hipStre
 {
     if (n_workgroups == 0) return hipSuccess;
     dim3 grid((unsigned)n_workgroups), block(512);
-    if (a.queue_workers > 0) {
-        if (dtype == PAT_F16)
-            hipLaunchKernelGGL(forward_queue_kernel<F16>, grid, block, 0, s, a);
-        else
-            hipLaunchKernelGGL(forward_queue_kernel<BF16>, grid, block, 0, s, a);
-    } else {
-        if (dtype == PAT_F16)
-            hipLaunchKernelGGL(forward_kernel<F16>, grid, block, 0, s, a);
-        else
-            hipLaunchKernelGGL(forward_kernel<BF16>, grid, block, 0, s, a);
-    }
-    return hipGetLastError();
+    FwdArgs args = a;
+    void *params[] = {&args};
+    const void *fn;
+    if (a.queue_workers > 0)
+        fn = dtype == PAT_F16 ? (const void *)forward_queue_kernel<F16> : (const void *)forward_queue_kernel<BF16>;
+    else
+        fn = dtype == PAT_F16 ? (const void *)forward_kernel<F16> : (const void *)forward_kernel<BF16>;
+    // the launch's own status: hipGetLastError() could hand back an unrelated earlier failure
+    return hipLaunchKernel(fn, grid, block, params, 0, s);
 }
 
 }  // namespace pat

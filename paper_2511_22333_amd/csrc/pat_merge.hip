@@ -171,18 +171,14 @@ hipError_t launch_merge(int dtype, const MergeArgs &a, hipStream_t s)
     if (a.n_merge == 0) return hipSuccess;
     const int units = a.n_merge * (a.long_lists ? a.Hq : (a.Hq + 1) / 2);
     dim3 grid((unsigned)((units + 3) / 4)), block(256);
-    if (a.long_lists) {
-        if (dtype == PAT_F16)
-            hipLaunchKernelGGL(merge_kernel_lists<F16>, grid, block, 0, s, a);
-        else
-            hipLaunchKernelGGL(merge_kernel_lists<BF16>, grid, block, 0, s, a);
-    } else {
-        if (dtype == PAT_F16)
-            hipLaunchKernelGGL(merge_kernel_pairs<F16>, grid, block, 0, s, a);
-        else
-            hipLaunchKernelGGL(merge_kernel_pairs<BF16>, grid, block, 0, s, a);
-    }
-    return hipGetLastError();
+    MergeArgs args = a;
+    void *params[] = {&args};
+    const void *fn;
+    if (a.long_lists)
+        fn = dtype == PAT_F16 ? (const void *)merge_kernel_lists<F16> : (const void *)merge_kernel_lists<BF16>;
+    else
+        fn = dtype == PAT_F16 ? (const void *)merge_kernel_pairs<F16> : (const void *)merge_kernel_pairs<BF16>;
+    return hipLaunchKernel(fn, grid, block, params, 0, s);
 }
 
 }  // namespace pat

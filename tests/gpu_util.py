@@ -8,7 +8,14 @@ from paper_2511_22333_amd import binding as pb
 from paper_2511_22333_amd import workloads as wl
 
 TOL = {"fp16": 2e-3, "bf16": 1e-2}      # max-abs error of out against the fp64 oracle
-LSE_TOL = 2e-3
+# lse: the scores are fp32 sums of exact 16-bit products and the sum of exponentials is fp32, so
+# the error is a few fp32 roundings of the score itself: 1e-4 absolute up to |lse| = 32, and in
+# proportion beyond (keys made 30-40 times louder push |lse| into the hundreds)
+LSE_TOL = 1e-4
+
+
+def lse_tol(want_lse):
+    return LSE_TOL * np.maximum(1.0, np.abs(want_lse) / 32.0)
 
 
 def run_hip(batch, tensors, *, with_lse=True, separate_stages=False, **plan_kw):
@@ -56,9 +63,35 @@ def compare(batch, out, lse, want, want_lse, req_ids=None):
         if req_ids is not None:
             gl = gl[np.asarray(req_ids)]
         assert np.isfinite(gl).all()
-        lerr = np.abs(gl - want_lse).max()
-        assert lerr <= LSE_TOL, f"lse error {lerr}"
+        diff = np.abs(gl - want_lse)
+        lerr = diff.max()
+        assert (diff <= lse_tol(want_lse)).all(), f"lse error {lerr} (|lse| up to {np.abs(want_lse).max():.1f})"
     return float(err), float(lerr)
+
+
+def compare_all_requests_in_groups(batch, out, lse, gpu_tensors, group=32):
+    """Every request of a batch whose pools live on the GPU against the oracle: the pages of
+    `group` requests at a time are gathered to the host (bounded host memory), the oracle attends
+    those requests one by one, and out/lse are compared element by element."""
+    q, kp, vp, st = gpu_tensors
+    qc = q.cpu()
+    P = batch.page_size
+    worst, worst_l = 0.0, 0.0
+    for g0 in range(0, batch.num_requests, group):
+        ids = list(range(g0, min(batch.num_requests, g0 + group)))
+        pages = np.unique(np.concatenate(
+            [batch.block_tables[r, : -(-int(batch.kv_lens[r]) // P)] for r in ids]))
+        remap = np.full(batch.num_pages, -1, np.int64)
+        remap[pages] = np.arange(len(pages))
+        idx = torch.from_numpy(pages.astype(np.int64)).to(kp.device)
+        bt = np.where(batch.block_tables >= 0, remap[np.maximum(batch.block_tables, 0)], -1)
+        sub = wl.DecodeBatch(batch.name, batch.num_requests, batch.num_q_heads,
+                             batch.num_kv_heads, batch.head_dim, P, batch.dtype,
+                             bt.astype(np.int32), batch.kv_lens, len(pages))
+        want, want_lse = run_oracle(sub, (qc, kp[idx].cpu(), vp[idx].cpu(), st), req_ids=ids)
+        e, l = compare(batch, out, lse, want, want_lse, req_ids=ids)
+        worst, worst_l = max(worst, e), max(worst_l, l)
+    return worst, worst_l
 
 
 def parity(batch, *, layout="NHD", poison=True, seed=None, **plan_kw):

@@ -297,6 +297,15 @@ def test_gpu_calls_refuse_a_plan_that_was_not_uploaded():
     assert pb.lib.pat_forward(None, 16, 16, 16, 8, 8, 8, 1.0, 16, None, 256, 1 << 20, None) == -1
 
 
+@pytest.mark.parametrize("scale", [0.0, -0.5, float("nan"), float("inf")])
+def test_forward_refuses_a_scale_that_is_not_positive_and_finite(scale):
+    # the packed tiles take row maxima on unscaled scores, which needs scale > 0
+    b = wl.config("C1")
+    plan = pb.plan_for_batch(b)
+    for fn in (pb.lib.pat_forward, pb.lib.pat_decode_attention):
+        assert fn(plan.handle, 16, 16, 16, 8, 8, 8, scale, 16, None, 256, 1 << 20, None) == -1
+
+
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "pat.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
