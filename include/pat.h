@@ -233,6 +233,21 @@ int pat_decode_attention(const pat_plan_t *plan, const void *q, const void *k_po
                          int64_t kv_stride_head, float softmax_scale, void *out, float *lse,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, serving loops
+ * and harnesses that forbid hipMalloc): pat_decode_attention() with the workspace taken from a
+ * fixed array of PAT_STATIC_WORKSPACE_BYTES inside the library's device image (every GPU the
+ * library runs on holds its own copy until the process ends).  q, pools, out, lse and the plan's
+ * uploaded buffer are the caller's as before.  Calls no allocating routine.  A plan whose
+ * stats.workspace_bytes exceeds the array is refused with PAT_ERR_WORKSPACE_TOO_SMALL and
+ * nothing is launched.  All calls on one GPU share the array: calls that overlap on one GPU (two
+ * streams, two threads) race; calls one after the other on one stream are fine, and nothing of
+ * an earlier call is read (the forward stage writes every partial the merge stage reads). */
+#define PAT_STATIC_WORKSPACE_BYTES (32u << 20)
+int pat_decode_attention_static_ws(const pat_plan_t *plan, const void *q, const void *k_pool,
+                                   const void *v_pool, int64_t kv_stride_page,
+                                   int64_t kv_stride_token, int64_t kv_stride_head,
+                                   float softmax_scale, void *out, float *lse, void *stream);
+
 /* Debug aid (the analogue of the paper's per-SM CTA timelines, sec. "Ablation Study").  While a
  * device buffer is set, every pat_forward() whose launch has at most bytes/64 workgroups writes
  * one record of eight uint64 per workgroup, in launch order: start and end time on the GPU's

@@ -78,7 +78,9 @@ class pat_plan_view(C.Structure):
 EXPORTED = ("pat_plan", "pat_plan_destroy", "pat_plan_get_stats", "pat_plan_export",
             "pat_plan_upload", "pat_num_tiles", "pat_tile_info", "pat_forward", "pat_merge",
             "pat_decode_attention", "pat_strerror", "pat_version", "pat_debug_set_trace",
-            "pat_plan_advance", "pat_plan_start", "pat_plan_finish")
+            "pat_plan_advance", "pat_plan_start", "pat_plan_finish",
+            "pat_decode_attention_static_ws")
+PAT_STATIC_WORKSPACE_BYTES = 32 << 20
 
 lib.pat_plan.argtypes = [C.POINTER(pat_batch_desc), C.POINTER(pat_plan_opts),
                          C.POINTER(C.c_void_p)]
@@ -101,6 +103,7 @@ _fwd_args = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int6
              C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 lib.pat_forward.argtypes = _fwd_args
 lib.pat_decode_attention.argtypes = _fwd_args
+lib.pat_decode_attention_static_ws.argtypes = _fwd_args[:10] + [C.c_void_p]
 lib.pat_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                           C.c_void_p]
 lib.pat_debug_set_trace.argtypes = [C.c_void_p, C.c_size_t]
@@ -297,6 +300,14 @@ def pat_decode_attention(plan, q, k_pool, v_pool, strides, scale, out, lse, work
                          stream=None):
     _fwd_call(lib.pat_decode_attention, "pat_decode_attention", plan, q, k_pool, v_pool, strides,
               scale, out, lse, workspace, stream)
+
+
+def pat_decode_attention_static_ws(plan, q, k_pool, v_pool, strides, scale, out, lse, stream=None):
+    _check(lib.pat_decode_attention_static_ws(
+        plan.handle, q.data_ptr(), k_pool.data_ptr(), v_pool.data_ptr(), int(strides[0]),
+        int(strides[1]), int(strides[2]), float(scale), out.data_ptr(),
+        lse.data_ptr() if lse is not None else None, _stream_ptr(stream)),
+        "pat_decode_attention_static_ws")
 
 
 def pat_merge(plan, out, lse, workspace, stream=None):

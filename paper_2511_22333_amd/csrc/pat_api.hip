@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <system_error>
 #include <thread>
@@ -294,6 +295,44 @@ int pat_decode_attention(const pat_plan_t *plan, const void *q, const void *k_po
                          stream);
     if (rc != PAT_OK) return rc;
     return pat_merge(plan, out, lse, workspace, workspace_bytes, stream);
+}
+
+// ---- the same step for callers that cannot allocate device memory -------------------------------
+// The workspace is a file-scope device array.  Its name is only a host-side handle: the address the
+// kernels are given comes from hipGetSymbolAddress, once per device (every GPU holds its own copy).
+static __device__ __align__(256) unsigned char scratch[PAT_STATIC_WORKSPACE_BYTES];
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[64] = {nullptr};
+
+static int static_workspace(void **ptr)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return PAT_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PAT_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return PAT_OK;
+}
+
+int pat_decode_attention_static_ws(const pat_plan_t *plan, const void *q, const void *k_pool,
+                                   const void *v_pool, int64_t kv_stride_page,
+                                   int64_t kv_stride_token, int64_t kv_stride_head,
+                                   float softmax_scale, void *out, float *lse, void *stream)
+{
+    if (!plan) return PAT_ERR_INVALID_ARG;
+    if ((size_t)plan->stats.workspace_bytes > (size_t)PAT_STATIC_WORKSPACE_BYTES)
+        return PAT_ERR_WORKSPACE_TOO_SMALL;
+    void *ws = nullptr;
+    const int rc = static_workspace(&ws);
+    if (rc != PAT_OK) return rc;
+    // every partial the merge reads is written by this call's forward first: nothing to clear
+    return pat_decode_attention(plan, q, k_pool, v_pool, kv_stride_page, kv_stride_token,
+                                kv_stride_head, softmax_scale, out, lse, ws,
+                                PAT_STATIC_WORKSPACE_BYTES, stream);
 }
 
 const char *pat_strerror(int status)
