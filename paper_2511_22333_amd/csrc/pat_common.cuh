@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "pat_internal.h"
@@ -45,6 +46,41 @@ template <> struct Elem<BF16> {
 // address space, which makes their (workgroup-uniform) loads scalar loads whatever else the
 // kernel stores in between.
 typedef __attribute__((address_space(4))) DevUnit ConstDevUnit;
+
+// The whole 128-byte unit record in scalar registers: two scalar loads and one wait, issued as
+// the first thing a workgroup does.  Every field a tile needs to send out its first K/V and q
+// loads is then there after ONE round trip; left to the compiler, the record's second cache line
+// (the inlined page and request ids) is fetched only when a tile first touches it, behind the
+// branches on the tile id, which costs a second dependent round trip before any data is asked for.
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+struct UnitRec {
+    i32x4 e0, e1, h, p0, p1, rq;            // six 16-byte pieces of the record's first 96 bytes
+    __device__ __forceinline__ int req_off() const { return e0[0]; }
+    __device__ __forceinline__ int n_req() const { return e0[1]; }
+    __device__ __forceinline__ int page_off() const { return e0[2]; }
+    __device__ __forceinline__ int n_pages() const { return e0[3]; }
+    __device__ __forceinline__ int kv_len() const { return e1[0]; }
+    __device__ __forceinline__ int row_begin() const { return e1[1]; }
+    __device__ __forceinline__ int n_rows() const { return e1[2]; }
+    __device__ __forceinline__ int tile() const { return e1[3]; }
+    __device__ __forceinline__ int kvh0() const { return h[0]; }
+    __device__ __forceinline__ int n_heads() const { return h[1]; }
+    // inlined ids: pages 0..7 and requests 0..3 of the entry
+    __device__ __forceinline__ int page(int i) const { return i < 4 ? p0[i] : p1[i - 4]; }
+    __device__ __forceinline__ int req(int i) const { return rq[i]; }
+};
+static_assert(offsetof(DevUnit, kvh0) == 32 && offsetof(DevUnit, page0) == 48 &&
+              offsetof(DevUnit, page4) == 64 && offsetof(DevUnit, req0) == 80, "UnitRec pieces");
+__device__ __forceinline__ void unit_fetch(const DevUnit *p, UnitRec &r)
+{
+    asm volatile("s_load_dwordx4 %0, %6, 0x0\n\ts_load_dwordx4 %1, %6, 0x10\n\t"
+                 "s_load_dwordx4 %2, %6, 0x20\n\ts_load_dwordx4 %3, %6, 0x30\n\t"
+                 "s_load_dwordx4 %4, %6, 0x40\n\ts_load_dwordx4 %5, %6, 0x50\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&s"(r.e0), "=&s"(r.e1), "=&s"(r.h), "=&s"(r.p0), "=&s"(r.p1), "=&s"(r.rq)
+                 : "s"(p)
+                 : "memory");
+}
 
 // Arguments common to every forward kernel.
 struct FwdArgs {

@@ -31,33 +31,32 @@ __device__ __forceinline__ void run_unit(const FwdArgs &a, int u, unsigned char 
     if (LOOPED) asm volatile("" : "+v"(tx));
     unsigned long long t_start = 0;
     if (a.trace) t_start = wall_clock64();
-    // The entry is copied into scalar registers; the inlined ids are read where they are
-    // needed, straight from the record (a copy of the whole 128-byte struct would end up in
-    // scratch memory once the tiles pick among its fields).
-    const ConstDevUnit *up = (const ConstDevUnit *)(a.units + u);
+    // The record goes into scalar registers in one round trip (see UnitRec).
+    UnitRec ur;
+    unit_fetch(a.units + u, ur);
     DevEntry ue;
-    ue.req_off = up->e.req_off;
-    ue.n_req = up->e.n_req;
-    ue.page_off = up->e.page_off;
-    ue.n_pages = up->e.n_pages;
-    ue.kv_len = up->e.kv_len;
-    ue.row_begin = up->e.row_begin;
-    ue.n_rows = up->e.n_rows;
-    ue.tile = up->e.tile;
-    const int kvh0 = up->kvh0, n_heads = up->n_heads;
+    ue.req_off = ur.req_off();
+    ue.n_req = ur.n_req();
+    ue.page_off = ur.page_off();
+    ue.n_pages = ur.n_pages();
+    ue.kv_len = ur.kv_len();
+    ue.row_begin = ur.row_begin();
+    ue.n_rows = ur.n_rows();
+    ue.tile = ur.tile();
+    const int kvh0 = ur.kvh0(), n_heads = ur.n_heads();
     const int tile = ue.tile;
     if (tile >= TILE_PACKED32) {
         if (tile == TILE_PACKED128)
-            tile_packed<T, 4>(a, ue, up, u, kvh0, tx, smem);
+            tile_packed<T, 4>(a, ue, ur, u, kvh0, tx, smem);
         else
-            tile_packed<T, 2>(a, ue, up, u, kvh0, tx, smem);
+            tile_packed<T, 2>(a, ue, ur, u, kvh0, tx, smem);
     } else {
         const int half = __builtin_amdgcn_readfirstlane(tx >> 8);
         const bool active = half < n_heads;
         const int kvh = kvh0 + (active ? half : 0);
         unsigned char *hsmem = smem + half * kHalfSmemBytes;
         if (tile == TILE_STREAM16)
-            tile_stream16<T>(a, ue, up, u, kvh, active, tx & 255, hsmem);
+            tile_stream16<T>(a, ue, ur, u, kvh, active, tx & 255, hsmem);
         else
             tile_valu16<T>(a, ue, kvh, active, tx & 255, hsmem);
     }

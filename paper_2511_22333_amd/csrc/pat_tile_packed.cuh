@@ -124,7 +124,6 @@ __device__ __forceinline__ void wait_loads_outstanding()
 // unclamped: a tile that straddles the end of the entry picks up the next entry's ids (or the
 // zeros the planner pads the list with), which are valid pages whose tokens are masked later;
 // tiles past the end are requested but never loaded.
-typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 struct PageIds {
     i32x4 id;
 };
@@ -158,7 +157,7 @@ __device__ __forceinline__ float max3(float a, float b, float c)
 }
 
 template <typename T, int ROW_WAVES>
-__device__ __forceinline__ void tile_packed(const FwdArgs &a, const DevEntry &e, const ConstDevUnit *up,
+__device__ __forceinline__ void tile_packed(const FwdArgs &a, const DevEntry &e, const UnitRec &up,
                                             int unit, int kvh, int tid, unsigned char *smem)
 {
     using namespace pk;
@@ -281,8 +280,8 @@ __device__ __forceinline__ void tile_packed(const FwdArgs &a, const DevEntry &e,
     const int q_row = e.row_begin + (live ? my_row : 0);
     static_assert(kUnitPages == 8, "two tiles of page ids in the unit record");
     PageIds first[3];
-    first[0].id = i32x4{up->page0, up->page1, up->page2, up->page3};
-    first[1].id = i32x4{up->page4, up->page5, up->page6, up->page7};
+    first[0].id = up.p0;
+    first[1].id = up.p1;
     page_ids_request(pages, 2, first[2]);
     const int q_req = a.req_ids[e.req_off + q_row / G];
     // Where the epilogue will put the rows this lane writes (row = lane / 4 of each 16-row

@@ -39,7 +39,7 @@ static_assert(4 * 16 * kOsRow * 4 <= kSlabBytes, "merge buffer aliases the slabs
 // through with nothing to load or store.
 template <typename T>
 __device__ __forceinline__ void tile_stream16(const FwdArgs &a, const DevEntry &e_in,
-                                              const ConstDevUnit *up, int unit, int kvh, bool active, int tid,
+                                              const UnitRec &up, int unit, int kvh, bool active, int tid,
                                               unsigned char *smem)
 {
     using namespace s16;
@@ -99,23 +99,18 @@ __device__ __forceinline__ void tile_stream16(const FwdArgs &a, const DevEntry &
     int stage = wave;
     const bool has_work = stage < n_stages;
     static_assert(kUnitPages == 8 && kUnitReqs == 4, "selects below");
-    const int first_pa = wave == 0 ? up->page0 : wave == 1 ? up->page2
-                       : wave == 2 ? up->page4 : up->page6;
-    const int first_pb = wave == 0 ? up->page1 : wave == 1 ? up->page3
-                       : wave == 2 ? up->page5 : up->page7;
-    // ids of the stage after that: always fetched one stage ahead, so that only the K/V loads
-    // themselves are a round trip the loop has to wait for
-    const bool has_second = stage + 4 < n_stages;
-    int next_pa = has_second ? pages[2 * (stage + 4)] : 0;
-    int next_pb = has_second ? pages[min(2 * (stage + 4) + 1, e.n_pages - 1)] : 0;
+    const int first_pa = wave == 0 ? up.page(0) : wave == 1 ? up.page(2)
+                       : wave == 2 ? up.page(4) : up.page(6);
+    const int first_pb = wave == 0 ? up.page(1) : wave == 1 ? up.page(3)
+                       : wave == 2 ? up.page(5) : up.page(7);
     // ---- Q^T operand: lane holds row l16, elements c*32 + grp*8 .. +8 of chunk c ------------
     u32x4 qop[4];
     {
         const bool live = l16 < e.n_rows;
         const int row = e.row_begin + (live ? l16 : 0);
         const int ri = row / G;                         // request position within the entry
-        int req = ri == 0 ? up->req0 : ri == 1 ? up->req1
-                : ri == 2 ? up->req2 : up->req3;
+        int req = ri == 0 ? up.req(0) : ri == 1 ? up.req(1)
+                : ri == 2 ? up.req(2) : up.req(3);
         if (e.n_req > kUnitReqs) req = a.req_ids[e.req_off + ri];          // uniform
         const int head = kvh * G + row % G;
         const uint16_t *qp = a.q + ((int64_t)req * a.Hq + head) * kHeadDim + grp * 8;
@@ -139,6 +134,12 @@ __device__ __forceinline__ void tile_stream16(const FwdArgs &a, const DevEntry &
 
     if (has_work) issue_loads(stage, first_pa, first_pb);
     tm.mark(a, 3);
+    // ids of the stage after that: always fetched one stage ahead, so that only the K/V loads
+    // themselves are a round trip the loop has to wait for (asked for after the first loads have
+    // gone out: nothing of the start-up waits for them)
+    const bool has_second = stage + 4 < n_stages;
+    int next_pa = has_second ? pages[2 * (stage + 4)] : 0;
+    int next_pb = has_second ? pages[min(2 * (stage + 4) + 1, e.n_pages - 1)] : 0;
 
     for (; stage < n_stages; stage += 4) {
         // ---- K: registers -> wavefront-private LDS slab (row = token, 272-byte pitch) -------
