@@ -117,6 +117,12 @@ typedef struct {
                                      /*   ns: packed workgroup = [0] + [1] * tokens, 16-row     */
                                      /*   workgroup = [2] + [3] * tokens * KV heads; all 0 =    */
                                      /*   the built-in MI355X calibration                       */
+    int32_t wave_kv_tokens;          /* 16-row packs of up to wave_max_tokens tokens are cut    */
+                                     /*   into parts of at most this many tokens, each (part,   */
+                                     /*   KV head) walked by ONE wavefront (tile n = 32).       */
+                                     /*   0 or negative = not used (the default: measured       */
+                                     /*   slower than n = 128 on MI355X)                        */
+    int32_t wave_max_tokens;         /* 0 = 4 * wave_kv_tokens                                  */
     int32_t reserved[1];             /* must be 0                                               */
 } pat_plan_opts;
 
@@ -125,14 +131,18 @@ typedef struct {
     int32_t num_packs;               /* packs after TreeHeuristic, before splitting             */
     int32_t num_merged_children;     /* children packed by Scheme 2                             */
     int32_t num_items;               /* work items after long-KV split                          */
-    int32_t num_entries;             /* (item, row block) units; workgroups = entries * Hkv     */
-    int32_t num_workgroups;
+    int32_t num_entries;             /* (item, row block) units                                 */
+    int32_t num_workgroups;          /* units of work of the forward launch                     */
     int32_t num_slots;               /* partial-result slots in the workspace                   */
     int32_t num_merge_requests;      /* requests with more than one partial                     */
     int64_t unique_kv_tokens;        /* sum of item kv_len = tokens read once by the forward    */
     int64_t total_kv_tokens;         /* sum of kv_lens = tokens a one-query-per-CTA kernel reads*/
     int64_t plan_device_bytes;       /* size pat_plan_upload() needs                            */
     int64_t workspace_bytes;         /* size forward/merge need                                 */
+    int32_t num_wave_items;          /* (entry, KV head) items walked by one wavefront each;    */
+                                     /*   num_workgroups counts them next to the workgroup-     */
+                                     /*   level units (one timeline record each)                */
+    int32_t num_workers;             /* persistent workgroups of a launch with such items, or 0 */
     int32_t tile_histogram[16];      /* entries per tile id                                     */
 } pat_plan_stats;
 

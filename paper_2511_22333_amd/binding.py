@@ -52,7 +52,8 @@ class pat_plan_opts(C.Structure):
     _fields_ = [("mode", C.c_int32), ("merge_factor", C.c_int32), ("split_policy", C.c_int32),
                 ("split_target_tokens", C.c_int32), ("force_tile", C.c_int32),
                 ("num_cus", C.c_int32), ("tail_reserve_pages", C.c_int32),
-                ("model_ns", C.c_int32 * 4), ("reserved", C.c_int32 * 1)]
+                ("model_ns", C.c_int32 * 4), ("wave_kv_tokens", C.c_int32),
+                ("wave_max_tokens", C.c_int32), ("reserved", C.c_int32 * 1)]
 
 
 class pat_plan_stats(C.Structure):
@@ -62,6 +63,7 @@ class pat_plan_stats(C.Structure):
                 ("num_slots", C.c_int32), ("num_merge_requests", C.c_int32),
                 ("unique_kv_tokens", C.c_int64), ("total_kv_tokens", C.c_int64),
                 ("plan_device_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
+                ("num_wave_items", C.c_int32), ("num_workers", C.c_int32),
                 ("tile_histogram", C.c_int32 * 16)]
 
 
@@ -196,7 +198,8 @@ def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, page_size: int, n
              num_q_heads: int, num_kv_heads: int, head_dim: int, dtype, mode: int = PAT_MODE_PAT,
              merge_factor: int = 0, split_policy: int = PAT_SPLIT_AUTO,
              split_target_tokens: int = 0, force_tile: int = -1, num_cus: int = 0,
-             tail_reserve_pages: int = 0, model_ns=None, background: bool = False, node_parent: Optional[np.ndarray] = None,
+             tail_reserve_pages: int = 0, model_ns=None, wave_kv_tokens: int = 0,
+             wave_max_tokens: int = 0, background: bool = False, node_parent: Optional[np.ndarray] = None,
              node_num_pages: Optional[np.ndarray] = None,
              req_leaf_node: Optional[np.ndarray] = None) -> Plan:
     bt = np.ascontiguousarray(block_tables, dtype=np.int32)
@@ -220,6 +223,7 @@ def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, page_size: int, n
     o.split_target_tokens, o.force_tile, o.num_cus = (int(split_target_tokens), int(force_tile),
                                                       int(num_cus))
     o.tail_reserve_pages = int(tail_reserve_pages)
+    o.wave_kv_tokens, o.wave_max_tokens = int(wave_kv_tokens), int(wave_max_tokens)
     if model_ns is not None:
         for i, x in enumerate(model_ns):
             o.model_ns[i] = int(x)

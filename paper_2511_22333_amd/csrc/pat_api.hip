@@ -257,7 +257,14 @@ int pat_forward(const pat_plan_t *plan, const void *q, const void *k_pool, const
     a.queue_begin = plan->queue_begin;
     a.queue_workers = plan->queue_workers;
     a.queue_ctr = reinterpret_cast<int32_t *>(const_cast<unsigned char *>(dev) + plan->layout.queue_ctr);
-    if (launch_forward(plan->dtype, a, plan->queue_begin + plan->queue_workers, s) != hipSuccess)
+    a.workers = nullptr;
+    a.wave_items = reinterpret_cast<const DevWaveItem *>(dev + plan->layout.wave_items);
+    int n_workgroups = plan->queue_begin + plan->queue_workers;
+    if (!plan->workers.empty()) {
+        a.workers = reinterpret_cast<const DevWorker *>(dev + plan->layout.workers);
+        n_workgroups = (int)plan->workers.size();
+    }
+    if (launch_forward(plan->dtype, a, n_workgroups, s) != hipSuccess)
         return PAT_ERR_HIP;
     return PAT_OK;
 }

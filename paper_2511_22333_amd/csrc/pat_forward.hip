@@ -18,6 +18,7 @@
 #include "pat_tile_packed.cuh"
 #include "pat_tile_stream16.cuh"
 #include "pat_tile_valu16.cuh"
+#include "pat_tile_wave16.cuh"
 
 namespace pat {
 
@@ -45,7 +46,7 @@ __device__ __forceinline__ void run_unit(const FwdArgs &a, int u, unsigned char 
     ue.tile = ur.tile();
     const int kvh0 = ur.kvh0(), n_heads = ur.n_heads();
     const int tile = ue.tile;
-    if (tile >= TILE_PACKED32) {
+    if (tile >= TILE_PACKED64) {
         if (tile == TILE_PACKED128)
             tile_packed<T, 4>(a, ue, ur, u, kvh0, tx, smem);
         else
@@ -116,6 +117,31 @@ __global__ __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(kVgprLimitAt
     }
 }
 
+// Launches that hold wavefront items (TILE_WAVE16): as many persistent workgroups as the planner
+// made lists for.  A workgroup first runs its workgroup-level units (packed tiles, long 16-row
+// streams) one after the other, then its eight wavefronts part ways, each walking its own list of
+// items; nothing waits for anything: the schedule is static.
+template <typename T>
+__global__ __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(kVgprLimitAttr))) void forward_worker_kernel(
+    FwdArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kFwdSmemBytes];
+    const int32_t *wrec = reinterpret_cast<const int32_t *>(a.workers + blockIdx.x);
+    const int unit_begin = __builtin_amdgcn_readfirstlane(wrec[0]);
+    const int unit_end = __builtin_amdgcn_readfirstlane(wrec[1]);
+    for (int u = unit_begin; u < unit_end; ++u) {
+        run_unit<T, true>(a, u, smem);
+        __syncthreads();                                // the tile's LDS is free again
+    }
+    int tx = threadIdx.x;
+    asm volatile("" : "+v"(tx));
+    const int wave = __builtin_amdgcn_readfirstlane(tx >> 6);
+    const int begin = __builtin_amdgcn_readfirstlane(wrec[2 + wave]);
+    const int end = __builtin_amdgcn_readfirstlane(wrec[3 + wave]);
+    if (begin < end)
+        wave_stream16<T>(a, begin, end, tx & 63, smem + wave * w16::kSlabBytes, a.n_units);
+}
+
 hipError_t launch_forward(int dtype, const FwdArgs &a, int n_workgroups, hipStream_t s)
 {
     if (n_workgroups == 0) return hipSuccess;
@@ -123,7 +149,9 @@ hipError_t launch_forward(int dtype, const FwdArgs &a, int n_workgroups, hipStre
     FwdArgs args = a;
     void *params[] = {&args};
     const void *fn;
-    if (a.queue_workers > 0)
+    if (a.workers)
+        fn = dtype == PAT_F16 ? (const void *)forward_worker_kernel<F16> : (const void *)forward_worker_kernel<BF16>;
+    else if (a.queue_workers > 0)
         fn = dtype == PAT_F16 ? (const void *)forward_queue_kernel<F16> : (const void *)forward_queue_kernel<BF16>;
     else
         fn = dtype == PAT_F16 ? (const void *)forward_kernel<F16> : (const void *)forward_kernel<BF16>;

@@ -15,7 +15,7 @@ namespace pat {
 enum TileId : int32_t {
     TILE_VALU16 = 0,     // rows <= 16, VALU dot products, 4 tokens per stage (reference tile)
     TILE_STREAM16 = 1,   // rows <= 16, MFMA, four independent wave streams of 32 tokens
-    TILE_PACKED32 = 2,   // rows <= 32, MFMA, K/V tile shared in LDS, waves split rows
+    TILE_WAVE16 = 2,     // rows <= 16, MFMA, one wavefront per (entry, KV head), 32-token stages
     TILE_PACKED64 = 3,
     TILE_PACKED128 = 4,
     NUM_TILES = 5
@@ -75,11 +75,33 @@ struct DevUnit {
 };
 static_assert(sizeof(DevUnit) == 128, "DevUnit is one 128-byte record");
 
+// One item of TILE_WAVE16: an entry's rows against one KV head, walked by a single wavefront.
+// 64 bytes; carries the entry's first two page ids (index 1 clamped to the last page) and, for
+// entries of one request, the request id and its partial slot, so that the first loads need this
+// record only.
+struct DevWaveItem {
+    int32_t req_off, n_req, page_off, n_pages, kv_len, row_begin, n_rows, kvh;
+    int32_t req0, slot0, page0, page1;
+    int32_t pad[4];
+};
+static_assert(sizeof(DevWaveItem) == 64, "DevWaveItem is one 64-byte record");
+
+// One persistent workgroup of a launch that holds wavefront items: first the workgroup-level
+// units [unit_begin, unit_end), one after the other, then wavefront w walks the wavefront items
+// [item_off[w], item_off[w + 1]).  64 bytes.
+struct DevWorker {
+    int32_t unit_begin, unit_end;
+    int32_t item_off[9];
+    int32_t pad[5];
+};
+static_assert(sizeof(DevWorker) == 64, "DevWorker is one 64-byte record");
+
 // Offsets (in bytes from the start of the uploaded buffer) of the device arrays.
 struct DevLayout {
     size_t units = 0, req_ids = 0, req_slot = 0, page_ids = 0;
     size_t merge_rec = 0, req_slot_off = 0, req_slot_ids = 0;
     size_t queue_ctr = 0;            // two counters of the 16-row unit queue (own 256 bytes)
+    size_t workers = 0, wave_items = 0;
     size_t total = 0;
 };
 
@@ -107,6 +129,10 @@ struct pat_plan_s {
     // Units [queue_begin, units.size()) are 16-row units taken from a queue by queue_workers
     // persistent workgroups; queue_begin == units.size(): every unit is a workgroup of its own.
     int32_t queue_begin = 0, queue_workers = 0;
+    // Launches with wavefront items run as `workers.size()` persistent workgroups instead.
+    std::vector<pat::DevWorker> workers;
+    std::vector<pat::DevWaveItem> wave_items;
+    std::vector<int32_t> item_wave_off, item_waves;   // CSR: the wavefront items of each item
     pat_plan_stats stats{};
     // device copy
     pat::DevLayout layout;

@@ -9,6 +9,7 @@
 //   * only pages a request fills completely can be shared;
 //   * packs without queries or pages are dropped.
 #include <algorithm>
+#include <climits>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -21,12 +22,12 @@ namespace pat {
 static const TileInfo kTiles[NUM_TILES] = {
     {16, 4, true},      // TILE_VALU16
     {16, 128, true},    // TILE_STREAM16
-    {32, 64, false},    // TILE_PACKED32
+    {16, 32, true},     // TILE_WAVE16
     {64, 64, true},     // TILE_PACKED64
     {128, 64, true},    // TILE_PACKED128
 };
 
-static bool g_tile_available[NUM_TILES] = {true, true, false, true, true};
+static bool g_tile_available[NUM_TILES] = {true, true, true, true, true};
 
 const TileInfo &tile_info(int id) { return kTiles[id]; }
 
@@ -34,6 +35,8 @@ void set_tile_available(int id, bool on) { g_tile_available[id] = on; }
 bool tile_available(int id) { return id >= 0 && id < NUM_TILES && g_tile_available[id]; }
 
 namespace {
+
+inline bool is_packed_tile(int32_t t) { return t >= TILE_PACKED64; }
 
 struct Node {
     int32_t parent = -1;
@@ -338,20 +341,33 @@ int validate(const pat_batch_desc &b)
     return PAT_OK;
 }
 
-// Tile selector (sec. "Multi-tile Kernel", "Deriving Q tile m"): the smallest available m that
-// holds the rows; above the largest m the rows are cut into equal blocks.
-int32_t select_tile(int32_t rows)
+// Tile selector (sec. "Multi-tile Kernel", "Tile Selection": m from the number of query rows, n
+// from the KV length).
+//   m: the smallest available m that holds the rows; above the largest m the caller cuts the rows
+//      into equal blocks.  For 17..32 rows a short node is cheaper as two 16-row blocks than as one
+//      64-row packed workgroup (start-up and epilogue of the packed tile outweigh reading the
+//      node twice through L2): the crossover, measured with the KV-length sweep of the
+//      calibration module, is kPackedMinTokens.
+//   n: the 16-row family has two KV tiles: n = 32 (TILE_WAVE16, one wavefront per item) for
+//      entries of up to `wave_kv` tokens where the launch runs many rounds (wave_kv = 0: never),
+//      n = 128 (TILE_STREAM16, four wavefronts per KV head) otherwise.
+constexpr int32_t kPackedMinTokens = 240;
+int32_t select_tile(int32_t rows, int32_t kv_len, int32_t wave_kv)
 {
+    if (rows <= 16 || (rows <= 32 && kv_len < kPackedMinTokens)) {
+        if (wave_kv > 0 && kv_len <= wave_kv && g_tile_available[TILE_WAVE16]) return TILE_WAVE16;
+        if (g_tile_available[TILE_STREAM16]) return TILE_STREAM16;
+    }
     int32_t best = -1;
     for (int32_t t = 0; t < NUM_TILES; ++t) {
-        if (!g_tile_available[t] || t == TILE_VALU16) continue;
+        if (!g_tile_available[t] || !is_packed_tile(t)) continue;
         if (kTiles[t].m >= rows && (best < 0 || kTiles[t].m < kTiles[best].m)) best = t;
     }
     if (best >= 0) return best;
-    // no MFMA tile holds the rows: the largest available one, else the VALU tile
+    // no packed tile holds the rows: the largest available one, else a 16-row tile
     for (int32_t t = NUM_TILES - 1; t >= 0; --t)
-        if (g_tile_available[t]) return t;
-    return TILE_VALU16;
+        if (g_tile_available[t] && is_packed_tile(t)) return t;
+    return g_tile_available[TILE_STREAM16] ? TILE_STREAM16 : TILE_VALU16;
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -413,12 +429,42 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     for (const Pack &p : packs) unique_tokens += p.kv_len;
 
     // ---- long-KV split -----------------------------------------------------------------
-    struct Item { int32_t pack, start, n_pages, kv_len, heads_per_wg; };
+    struct Item { int32_t pack, start, n_pages, kv_len, heads_per_wg; bool wave; };
     std::vector<Item> items;
+    // Run-time model (ns) of the device-aware split and of the static schedule of launches with
+    // wavefront items, measured on MI355X with every CU busy (L = tokens, h = KV heads):
+    //   packed workgroup : 13000 + 26 L     (first tile late, tiles computed in turn, many
+    //                                        partial rows to write); 64-row tile: 0.73 and 0.90 of it
+    //   16-row workgroup :  4000 + 20 h L   (its share of the HBM stream)
+    //   wavefront item   :  1500 + 160 L    (an eighth of a CU's stream; start-up hidden)
+    const bool own_model = o.model_ns[0] || o.model_ns[1] || o.model_ns[2] || o.model_ns[3];
+    const int64_t c0p = own_model ? o.model_ns[0] : 13000, c1p = own_model ? o.model_ns[1] : 26;
+    const int64_t c0q = c0p * 73 / 100, c1q = std::max<int64_t>(1, c1p * 90 / 100);
+    const int64_t c0s = own_model ? o.model_ns[2] : 4000, c1s = own_model ? o.model_ns[3] : 20;
+    const int64_t c0w = 1500, c1w = 8 * c1s;
+    // TILE_WAVE16 (n = 32, one wavefront per item): where 16-row packs of a launch of many rounds
+    // are short.  wave_kv = longest item, wave_max = longest pack that is cut into such items.
+    int32_t wave_kv = 0, wave_max = 0;
+    if (o.force_tile == TILE_WAVE16) {
+        wave_kv = wave_max = INT32_MAX;
+    } else if (o.force_tile < 0 && o.wave_kv_tokens >= 0 && g_tile_available[TILE_WAVE16]) {
+        const bool many_rounds = (unique_tokens * b.num_kv_heads + (o.num_cus > 0 ? o.num_cus : 256) - 1) /
+                                 (o.num_cus > 0 ? o.num_cus : 256) > 1024;
+        // Measured on MI355X (C3, C4 and a KV-length sweep): with items of 128..512 tokens the
+        // n = 32 tile is 3..20 % slower than the n = 128 tile on these batches -- the streams of
+        // eight independent wavefronts per CU crowd the packed tiles' loads out of the memory
+        // system.  So it is used where the caller asks for it, not by default.
+        (void)many_rounds;
+        if (o.wave_kv_tokens > 0) {
+            wave_kv = o.wave_kv_tokens;
+            wave_max = o.wave_max_tokens > 0 ? o.wave_max_tokens : 4 * wave_kv;
+        }
+    }
     {
         // Per pack: into how many parts its KV range is cut, and how many KV heads one
-        // workgroup of a 16-row tile serves (2 = one per 256-thread half, 1 = second half idle).
-        struct Cut { int64_t parts; int32_t heads_per_wg; };
+        // workgroup of a 16-row tile serves (2 = one per 256-thread half, 1 = second half idle);
+        // wave: the parts run as wavefront items.
+        struct Cut { int64_t parts; int32_t heads_per_wg; bool wave = false; };
         std::vector<Cut> cuts(packs.size(), Cut{1, 2});
         auto parts_for = [](const Pack &p, int64_t num, int64_t den) {     // ceil(len / (num/den))
             int64_t parts = 1;
@@ -440,11 +486,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
             // run at once and share the HBM bandwidth evenly.
             // Small batches run as ONE round: the smallest bound on a workgroup's run time for
             // which the workgroups still fit the slots, so that nothing waits for a second
-            // round and all workgroups end together.  Run times follow a model measured on
-            // MI355X with every CU busy (ns; L = tokens, h = KV heads of the workgroup):
-            //   packed workgroup : 13000 + 26 L     (first tile late, tiles computed in turn,
-            //                                        many partial rows to write)
-            //   16-row workgroup :  4000 + 20 h L   (its share of the HBM stream)
+            // round and all workgroups end together.  Run times follow the model above.
             // A 16-row pack over the bound first goes to one head per workgroup (more CUs, no
             // extra partials), then its KV range is cut.
             // Large batches run many rounds; there two cuts are compared under the same model
@@ -454,15 +496,13 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
             for (int32_t t = 0; t < NUM_TILES; ++t)
                 if (g_tile_available[t]) max_m = std::max(max_m, kTiles[t].m);
             const int64_t Hkv = b.num_kv_heads, pair_wgs = (Hkv + 1) / 2;
-            const bool own_model = o.model_ns[0] || o.model_ns[1] || o.model_ns[2] || o.model_ns[3];
-            const int64_t c0p = own_model ? o.model_ns[0] : 13000, c1p = own_model ? o.model_ns[1] : 26;
-            // the 64-row packed tile (one computing wavefront per SIMD, half the rows to write):
-            // its fitted constants are 0.73 and 0.90 of the 128-row tile's
-            const int64_t c0q = c0p * 73 / 100, c1q = std::max<int64_t>(1, c1p * 90 / 100);
             auto packed_c0 = [&](const Pack &p) { return (int64_t)p.reqs.size() * G <= 64 ? c0q : c0p; };
             auto packed_c1 = [&](const Pack &p) { return (int64_t)p.reqs.size() * G <= 64 ? c1q : c1p; };
-            const int64_t c0s = own_model ? o.model_ns[2] : 4000, c1s = own_model ? o.model_ns[3] : 20;
-            auto is_packed = [&](const Pack &p) { return (int64_t)p.reqs.size() * G > 16; };
+            auto is_packed = [&](const Pack &p) {
+                const int64_t rows = (int64_t)p.reqs.size() * G;
+                return rows > 32 || (rows > 16 && p.kv_len >= kPackedMinTokens);
+            };
+            auto is_wave = [&](const Pack &p) { return !is_packed(p) && wave_kv > 0 && p.kv_len <= wave_max; };
             // bound = run time in ns a workgroup may take
             auto cut_for = [&](const Pack &p, int64_t bound, bool single_heads) {
                 if (is_packed(p))
@@ -480,7 +520,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
                     const Cut c = cut_for(p, bound, single_heads);
                     const int64_t rows = (int64_t)p.reqs.size() * G;
                     const int64_t wgs = is_packed(p) ? Hkv : (c.heads_per_wg == 1 ? Hkv : pair_wgs);
-                    n += c.parts * ((rows + max_m - 1) / max_m) * wgs;
+                    n += c.parts * (is_packed(p) ? (rows + max_m - 1) / max_m : (rows + 15) / 16) * wgs;
                 }
                 return n;
             };
@@ -498,14 +538,17 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
                 //           launch is estimated to take is cut, into parts that do not;
                 //   fine:   a pack is cut where it exceeds half a slot's share of all
                 //           token-heads, whatever its tile.
+                // (wavefront items are played as workgroups that hold eight of them side by side)
                 auto wg_ns = [&](const Pack &p, const Cut &c) {
                     const int64_t L = (p.kv_len + c.parts - 1) / c.parts;
+                    if (c.wave) return c0w + c1w * L;
                     return is_packed(p) ? packed_c0(p) + packed_c1(p) * L : c0s + c.heads_per_wg * c1s * L;
                 };
                 auto wg_count = [&](const Pack &p, const Cut &c) {
                     const int64_t rows = (int64_t)p.reqs.size() * G;
+                    if (c.wave) return (c.parts * ((rows + 15) / 16) * Hkv + 7) / 8;
                     const int64_t wgs = is_packed(p) ? Hkv : (c.heads_per_wg == 1 ? Hkv : pair_wgs);
-                    return c.parts * ((rows + max_m - 1) / max_m) * wgs;
+                    return c.parts * (is_packed(p) ? (rows + max_m - 1) / max_m : (rows + 15) / 16) * wgs;
                 };
                 auto launch_ns = [&](const std::vector<Cut> &cs) {
                     std::vector<std::pair<int64_t, int64_t>> jobs;          // (run time, how many)
@@ -527,12 +570,17 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
                 std::vector<Cut> fine(packs.size(), Cut{1, 2}), coarse(packs.size(), Cut{1, 2});
                 int64_t total_ns = 0;
                 for (size_t i = 0; i < packs.size(); ++i) {
-                    fine[i].parts = parts_for(packs[i], (share + 1) / 2, 1);
+                    if (is_wave(packs[i])) {
+                        fine[i] = coarse[i] = Cut{parts_for(packs[i], wave_kv, 1), 1, true};
+                    } else {
+                        fine[i].parts = parts_for(packs[i], (share + 1) / 2, 1);
+                    }
                     total_ns += wg_ns(packs[i], coarse[i]) * wg_count(packs[i], coarse[i]);
                 }
                 const int64_t whole = (total_ns + slots - 1) / slots;         // the launch, if it packed perfectly
                 for (size_t i = 0; i < packs.size(); ++i) {
                     const Pack &p = packs[i];
+                    if (coarse[i].wave) continue;
                     if (wg_ns(p, coarse[i]) * 100 <= whole * 115) continue;    // (the estimate is no better than that)
                     const int64_t c0 = is_packed(p) ? packed_c0(p) : c0s, c1 = is_packed(p) ? packed_c1(p) : 2 * c1s;
                     coarse[i].parts = parts_for(p, std::max<int64_t>(whole - c0, 64 * c1), c1);
@@ -562,6 +610,19 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
             break;
         }
         }
+        if (wave_kv > 0)
+            for (size_t i = 0; i < packs.size(); ++i) {
+                const Pack &p = packs[i];
+                const int64_t rows = (int64_t)p.reqs.size() * G;
+                const bool packed = rows > 32 || (rows > 16 && p.kv_len >= kPackedMinTokens);
+                if (cuts[i].wave || o.force_tile == TILE_WAVE16) {
+                    cuts[i].wave = true;
+                } else if (!packed && p.kv_len <= wave_max && o.wave_kv_tokens > 0) {
+                    // an explicit wave_kv_tokens: whatever the policy cut, cut again where needed
+                    cuts[i].parts = std::max(cuts[i].parts, parts_for(p, wave_kv, 1));
+                    cuts[i].wave = true;
+                }
+            }
         for (int32_t pi = 0; pi < (int32_t)packs.size(); ++pi) {
             const Pack &p = packs[pi];
             const int64_t parts = cuts[pi].parts;
@@ -571,7 +632,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
                 int32_t n = base + (i < extra ? 1 : 0);
                 int32_t end_tok = (start + n - p.start) * P;
                 int32_t tok = std::min(p.kv_len, end_tok) - (start - p.start) * P;
-                items.push_back({pi, start, n, tok, cuts[pi].heads_per_wg});
+                items.push_back({pi, start, n, tok, cuts[pi].heads_per_wg, cuts[pi].wave});
                 start += n;
             }
         }
@@ -647,32 +708,38 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     // ---- entries: row blocks + tiles -------------------------------------------------------
     struct E { int32_t item, row_begin, n_rows, tile; };
     std::vector<E> es;
+    std::vector<char> item_wave;
+    for (int32_t k = 0; k < n_items; ++k) item_wave.push_back(items[perm[k]].wave ? 1 : 0);
     for (int32_t k = 0; k < n_items; ++k) {
         int32_t n_req = pl.item_req_off[k + 1] - pl.item_req_off[k];
         int32_t rows = n_req * G;
-        int32_t tile = o.force_tile >= 0 ? o.force_tile : select_tile(rows);
+        const int32_t len = pl.item_kv_len[k];
+        const int32_t wkv = item_wave[k] ? INT32_MAX : 0;
+        int32_t tile = o.force_tile >= 0 ? o.force_tile : select_tile(rows, len, wkv);
         int32_t m = kTiles[tile].m;
         int32_t blocks = (rows + m - 1) / m;
         int32_t per = (rows + blocks - 1) / blocks;
-        if (o.force_tile < 0 && blocks > 1) {
+        if (o.force_tile < 0 && blocks > 1 && is_packed_tile(tile)) {
             // equal blocks may fit a smaller tile than the largest one
-            int32_t t2 = select_tile(per);
-            if (kTiles[t2].m >= per) { tile = t2; m = kTiles[t2].m; }
+            int32_t t2 = select_tile(per, len, 0);
+            if (is_packed_tile(t2) && kTiles[t2].m >= per) { tile = t2; m = kTiles[t2].m; }
         }
         for (int32_t rb = 0; rb < rows; rb += per)
             es.push_back({k, rb, std::min(per, rows - rb), tile});
     }
     // launch order: longest-running first, priced as the cuts were (bytes; a packed workgroup
     // a quarter above its bytes)
-    auto heads_of = [&](const E &x) { return x.tile >= TILE_PACKED32 ? 1 : item_heads[x.item]; };
+    auto heads_of = [&](const E &x) {
+        return is_packed_tile(x.tile) || x.tile == TILE_WAVE16 ? 1 : item_heads[x.item];
+    };
     auto cost = [&](const E &x) {
         const int64_t len = pl.item_kv_len[x.item];
-        return x.tile >= TILE_PACKED32 ? 5 * len : 4 * heads_of(x) * len;
+        return is_packed_tile(x.tile) ? 5 * len : 4 * heads_of(x) * len;
     };
     std::stable_sort(es.begin(), es.end(),
                      [&](const E &a, const E &c) { return cost(a) > cost(c); });
     std::memset(&pl.stats, 0, sizeof pl.stats);
-    std::vector<std::vector<int32_t>> units_of_item(n_items);
+    std::vector<int32_t> unit_item, wave_item_of;       // the item of every unit / wavefront item
     for (const E &e : es) {
         pl.entry_item.push_back(e.item);
         pl.entry_row_begin.push_back(e.row_begin);
@@ -689,6 +756,23 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
         d.n_rows = e.n_rows;
         d.tile = e.tile;
         pl.stats.tile_histogram[e.tile]++;
+        if (e.tile == TILE_WAVE16) {
+            // one wavefront item per KV head
+            for (int32_t h = 0; h < pl.Hkv; ++h) {
+                DevWaveItem w;
+                std::memset(&w, 0, sizeof w);
+                w.req_off = d.req_off; w.n_req = d.n_req; w.page_off = d.page_off;
+                w.n_pages = d.n_pages; w.kv_len = d.kv_len; w.row_begin = d.row_begin;
+                w.n_rows = d.n_rows; w.kvh = h;
+                w.req0 = pl.item_req_ids[d.req_off];
+                w.slot0 = pl.item_req_slot[d.req_off];
+                w.page0 = pl.pool_ids[d.page_off];
+                w.page1 = pl.pool_ids[d.page_off + std::min(1, d.n_pages - 1)];
+                wave_item_of.push_back(e.item);
+                pl.wave_items.push_back(w);
+            }
+            continue;
+        }
         // workgroups of this entry: one per KV head for packed tiles; the 16-row tiles run a
         // head per 256-thread half, so one per pair of KV heads unless the cut asked for one
         const int32_t per_wg = heads_of(e);
@@ -705,21 +789,104 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
                 *unit_pages[i] = pl.pool_ids[d.page_off + std::min(i, d.n_pages - 1)];
             for (int32_t i = 0; i < kUnitReqs; ++i)
                 *unit_reqs[i] = pl.item_req_ids[d.req_off + std::min(i, d.n_req - 1)];
-            units_of_item[e.item].push_back((int32_t)pl.units.size());
+            unit_item.push_back(e.item);
             pl.units.push_back(u);
         }
     }
-    // Long 16-row units at the end of a launch of many rounds are not workgroups of their own: as
-    // many persistent workgroups as there are CUs take them from a queue in the same order,
-    // which saves a workgroup launch per unit (C5: 3 %).  Short units stay workgroups: drawing
-    // from the queue costs an atomic's round trip per unit (C4 was 1 % slower with a queue).
     pl.queue_begin = (int32_t)pl.units.size();
     pl.queue_workers = 0;
-    {
-        const int32_t cus = o.num_cus > 0 ? o.num_cus : 256;
+    const int32_t cus = o.num_cus > 0 ? o.num_cus : 256;
+    if (!pl.wave_items.empty()) {
+        // Static schedule of a launch with wavefront items: `cus` persistent workgroups.  The
+        // workgroup-level units go to the workgroup that is free first, longest first, by the
+        // run-time model; then the wavefront items go, longest first, to the wavefront that is
+        // free first, a workgroup's eight wavefronts starting when its units are done.
+        auto unit_ns = [&](const DevUnit &u) {
+            if (is_packed_tile(u.e.tile))
+                return (u.e.n_rows <= 64 ? c0q : c0p) + (u.e.n_rows <= 64 ? c1q : c1p) * (int64_t)u.e.kv_len;
+            return c0s + c1s * u.n_heads * (int64_t)u.e.kv_len;
+        };
+        const int32_t n_workers = cus;
+        typedef std::pair<int64_t, int32_t> Slot;                 // (free at, index)
+        std::vector<int32_t> order(pl.units.size());
+        std::iota(order.begin(), order.end(), 0);
+        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+            return unit_ns(pl.units[x]) > unit_ns(pl.units[y]);
+        });
+        // The launch, if it packed perfectly.  Units are packed first-fit (longest first) into
+        // workgroups of that capacity rather than spread evenly: workgroups then either run units
+        // for the whole launch or walk wavefront items from its start, so that the streams of the
+        // items and the (often compute-bound) packed tiles share the memory system all the time
+        // instead of one after the other.
+        int64_t total_ns = 0;
+        for (const DevUnit &u : pl.units) total_ns += unit_ns(u);
+        for (const DevWaveItem &w : pl.wave_items) total_ns += (c0w + c1w * (int64_t)w.kv_len) / 8;
+        const int64_t ideal = (total_ns + n_workers - 1) / n_workers;
+        std::vector<std::vector<int32_t>> wg_units(n_workers);
+        std::vector<int64_t> wg_free(n_workers, 0);
+        for (int32_t x : order) {
+            const int64_t t = unit_ns(pl.units[x]);
+            int32_t best = -1;
+            for (int32_t w = 0; w < n_workers && best < 0; ++w)
+                if (wg_free[w] + t <= std::max(ideal, t)) best = w;
+            if (best < 0)
+                best = (int32_t)(std::min_element(wg_free.begin(), wg_free.end()) - wg_free.begin());
+            wg_units[best].push_back(x);
+            wg_free[best] += t;
+        }
+        std::priority_queue<Slot, std::vector<Slot>, std::greater<Slot>> free_wave;
+        for (int32_t w = 0; w < n_workers; ++w)
+            for (int32_t v = 0; v < 8; ++v) free_wave.push({wg_free[w], w * 8 + v});
+        std::vector<int32_t> worder(pl.wave_items.size());
+        std::iota(worder.begin(), worder.end(), 0);
+        std::stable_sort(worder.begin(), worder.end(), [&](int32_t x, int32_t y) {
+            return pl.wave_items[x].kv_len > pl.wave_items[y].kv_len;
+        });
+        std::vector<std::vector<int32_t>> wave_lists((size_t)n_workers * 8);
+        for (int32_t x : worder) {
+            Slot sl = free_wave.top();
+            free_wave.pop();
+            wave_lists[sl.second].push_back(x);
+            sl.first += c0w + c1w * (int64_t)pl.wave_items[x].kv_len;
+            free_wave.push(sl);
+        }
+        // lay units and items out in that order
+        std::vector<DevUnit> units2;
+        std::vector<int32_t> unit_item2;
+        std::vector<DevWaveItem> items2;
+        std::vector<int32_t> wave_item_of2;
+        pl.workers.assign(n_workers, DevWorker{});
+        for (int32_t w = 0; w < n_workers; ++w) {
+            DevWorker &wk = pl.workers[w];
+            std::memset(&wk, 0, sizeof wk);
+            wk.unit_begin = (int32_t)units2.size();
+            for (int32_t x : wg_units[w]) {
+                units2.push_back(pl.units[x]);
+                unit_item2.push_back(unit_item[x]);
+            }
+            wk.unit_end = (int32_t)units2.size();
+            for (int32_t v = 0; v < 8; ++v) {
+                wk.item_off[v] = (int32_t)items2.size();
+                for (int32_t x : wave_lists[(size_t)w * 8 + v]) {
+                    items2.push_back(pl.wave_items[x]);
+                    wave_item_of2.push_back(wave_item_of[x]);
+                }
+            }
+            wk.item_off[8] = (int32_t)items2.size();
+        }
+        pl.units.swap(units2);
+        unit_item.swap(unit_item2);
+        pl.wave_items.swap(items2);
+        wave_item_of.swap(wave_item_of2);
+        pl.queue_begin = (int32_t)pl.units.size();
+    } else {
+        // Long 16-row units at the end of a launch of many rounds are not workgroups of their own: as
+        // many persistent workgroups as there are CUs take them from a queue in the same order,
+        // which saves a workgroup launch per unit (C5: 3 %).  Short units stay workgroups: drawing
+        // from the queue costs an atomic's round trip per unit (C4 was 1 % slower with a queue).
         int32_t last_packed = -1;
         for (int32_t u = 0; u < (int32_t)pl.units.size(); ++u)
-            if (pl.units[u].e.tile >= TILE_PACKED32) last_packed = u;
+            if (is_packed_tile(pl.units[u].e.tile)) last_packed = u;
         const int32_t queued = (int32_t)pl.units.size() - (last_packed + 1);
         int64_t token_heads = 0;
         for (int32_t u = last_packed + 1; u < (int32_t)pl.units.size(); ++u)
@@ -729,10 +896,19 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
             pl.queue_workers = cus;
         }
     }
-    pl.item_unit_off.assign(1, 0);
-    for (int32_t k = 0; k < n_items; ++k) {
-        for (int32_t x : units_of_item[k]) pl.item_units.push_back(x);
-        pl.item_unit_off.push_back((int32_t)pl.item_units.size());
+    // CSR: the units and the wavefront items of each item (for pat_plan_advance)
+    {
+        std::vector<std::vector<int32_t>> of_item(n_items), waves_of_item(n_items);
+        for (size_t x = 0; x < unit_item.size(); ++x) of_item[unit_item[x]].push_back((int32_t)x);
+        for (size_t x = 0; x < wave_item_of.size(); ++x) waves_of_item[wave_item_of[x]].push_back((int32_t)x);
+        pl.item_unit_off.assign(1, 0);
+        pl.item_wave_off.assign(1, 0);
+        for (int32_t k = 0; k < n_items; ++k) {
+            for (int32_t x : of_item[k]) pl.item_units.push_back(x);
+            pl.item_unit_off.push_back((int32_t)pl.item_units.size());
+            for (int32_t x : waves_of_item[k]) pl.item_waves.push_back(x);
+            pl.item_wave_off.push_back((int32_t)pl.item_waves.size());
+        }
     }
 
     // ---- device image ----------------------------------------------------------------------
@@ -747,6 +923,8 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     L.req_slot_off = place(pl.req_slot_off.size() * 4);
     L.req_slot_ids = place(pl.req_slot_ids.size() * 4);
     L.queue_ctr = place(256);
+    L.workers = place(pl.workers.size() * sizeof(DevWorker));
+    L.wave_items = place(pl.wave_items.size() * sizeof(DevWaveItem));
     L.total = std::max<size_t>(off, 256);
     pl.staging.assign(L.total, 0);
     auto put = [&](size_t at, const void *src, size_t bytes) {
@@ -757,12 +935,14 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     put(L.req_slot, pl.item_req_slot.data(), pl.item_req_slot.size() * 4);
     put(L.page_ids, pl.pool_ids.data(), pl.pool_ids.size() * 4);
     put(L.req_slot_off, pl.req_slot_off.data(), pl.req_slot_off.size() * 4);
+    put(L.workers, pl.workers.data(), pl.workers.size() * sizeof(DevWorker));
+    put(L.wave_items, pl.wave_items.data(), pl.wave_items.size() * sizeof(DevWaveItem));
     {
         // device copy of the merge lists: bit 30 marks partials the packed tiles wrote with the
         // head dimension in their internal order (see kPartialPermutedBit)
         std::vector<char> permuted((size_t)n_slots, 0);
         for (size_t e = 0; e < pl.entry_item.size(); ++e) {
-            if (pl.entry_tile[e] < TILE_PACKED32) continue;
+            if (!is_packed_tile(pl.entry_tile[e])) continue;
             const int32_t k = pl.entry_item[e];
             for (int32_t i = pl.item_req_off[k]; i < pl.item_req_off[k + 1]; ++i)
                 if (pl.item_req_slot[i] >= 0) permuted[pl.item_req_slot[i]] = 1;
@@ -795,7 +975,9 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     s.num_merged_children = pk.merged_children;
     s.num_items = n_items;
     s.num_entries = (int32_t)pl.entry_item.size();
-    s.num_workgroups = (int32_t)pl.units.size();
+    s.num_workgroups = (int32_t)(pl.units.size() + pl.wave_items.size());
+    s.num_wave_items = (int32_t)pl.wave_items.size();
+    s.num_workers = (int32_t)pl.workers.size();
     s.num_slots = n_slots;
     s.num_merge_requests = (int32_t)pl.merge_req.size();
     s.unique_kv_tokens = unique_tokens;
@@ -829,6 +1011,7 @@ int advance_plan(pat_plan_s &pl, const int32_t *new_kv_lens, const int32_t *bloc
     unsigned char *img = pl.staging.data();
     int32_t *img_pages = reinterpret_cast<int32_t *>(img + pl.layout.page_ids);
     DevUnit *img_units = reinterpret_cast<DevUnit *>(img + pl.layout.units);
+    DevWaveItem *img_waves = reinterpret_cast<DevWaveItem *>(img + pl.layout.wave_items);
     for (int32_t r = 0; r < B; ++r) {
         const int32_t old_len = pl.kv_lens[r], new_len = new_kv_lens[r];
         if (new_len == old_len) continue;
@@ -860,6 +1043,14 @@ int advance_plan(pat_plan_s &pl, const int32_t *new_kv_lens, const int32_t *bloc
             for (int32_t i = 0; i < kUnitPages; ++i)
                 *unit_pages[i] = pl.pool_ids[base + std::min(i, n - 1)];
             img_units[pl.item_units[x]] = u;
+        }
+        for (int32_t x = pl.item_wave_off[k]; x < pl.item_wave_off[k + 1]; ++x) {
+            DevWaveItem &w = pl.wave_items[pl.item_waves[x]];
+            w.n_pages = n;
+            w.kv_len = pl.item_kv_len[k];
+            w.page0 = pl.pool_ids[base];
+            w.page1 = pl.pool_ids[base + std::min(1, n - 1)];
+            img_waves[pl.item_waves[x]] = w;
         }
         pl.view_dirty = true;
     }

@@ -76,7 +76,7 @@ def test_result_does_not_depend_on_the_plan(mode, policy, target):
     parity(b, mode=mode, split_policy=policy, split_target_tokens=target)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 3, 4])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 def test_every_tile_gives_the_same_attention(tile):
     # force_tile runs the whole batch through one tile family (rows are cut to its m)
     _log(f"case force_tile={tile}")
@@ -87,7 +87,7 @@ def test_every_tile_gives_the_same_attention(tile):
     assert hist[tile] == plan.stats().num_entries
 
 
-@pytest.mark.parametrize("s_req", [5, 24])          # 20 rows -> 64-row tile, 96 rows -> 128-row tile
+@pytest.mark.parametrize("s_req", [9, 24])          # 36 rows -> 64-row tile, 96 rows -> 128-row tile
 @pytest.mark.parametrize("node_tokens", [16, 32, 48, 64, 80, 128, 144, 192, 208, 256, 272, 336, 528])
 def test_packed_tiles_over_tile_counts(node_tokens, s_req):
     # one shared node of 1..9 tiles (a page count that is no multiple of four ends in a
@@ -97,11 +97,11 @@ def test_packed_tiles_over_tile_counts(node_tokens, s_req):
                       num_q_heads=8, num_kv_heads=2, dtype="bf16", seed=node_tokens + s_req)
     (_, _), plan = parity(b, split_policy=pb.PAT_SPLIT_NONE)
     hist = list(plan.stats().tile_histogram)
-    assert hist[3 if s_req == 5 else 4] == 1
+    assert hist[3 if s_req == 9 else 4] == 1
 
 
 @pytest.mark.parametrize("loud_half", [0, 1])
-@pytest.mark.parametrize("s_req", [5, 24])
+@pytest.mark.parametrize("s_req", [9, 24])
 def test_packed_tile_row_maximum_spans_both_token_halves(s_req, loud_half):
     # The packed tile splits the 32 tokens a wavefront handles over its two lane halves (half h
     # holds tokens 4h .. 4h + 3 of every eight); the running maximum has to be the maximum over
@@ -120,11 +120,11 @@ def test_packed_tile_row_maximum_spans_both_token_halves(s_req, loud_half):
                 kp[pid, t] *= 40.0
     want, want_lse = run_oracle(b, (q, kp, vp, strides))
     out, lse, plan = run_hip(b, to_gpu((q, kp, vp, strides)), split_policy=pb.PAT_SPLIT_NONE)
-    assert list(plan.stats().tile_histogram)[3 if s_req == 5 else 4] == 1
+    assert list(plan.stats().tile_histogram)[3 if s_req == 9 else 4] == 1
     compare(b, out, lse, want, want_lse)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 3, 4])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("kind", ["loud", "identical"])
 def test_extreme_scores_on_every_tile(tile, kind):
     # loud: keys 30 times N(0,1), so the softmax is close to one-hot and scores differ by hundreds;
@@ -158,6 +158,49 @@ def test_merge_mappings_for_short_and_long_partial_lists(lens):
     assert n_parts.max() == -(-max(lens) // 16)
 
 
+@pytest.mark.parametrize("layout", ["NHD", "HND"])
+@pytest.mark.parametrize("wave_kv", [16, 48, 100000])
+def test_wavefront_items_on_forests(wave_kv, layout):
+    # the 16-row packs of a forest cut into parts of at most wave_kv tokens, every (part, KV head)
+    # walked by one wavefront of a persistent workgroup next to the packed tiles of the shared
+    # nodes: parts of one stage, of several stages with a ragged last one, and whole packs
+    for seed in (3, 4, 8):
+        b = wl.random_forest_batch(seed, dtype="bf16" if seed % 2 else "fp16", max_requests=40,
+                                   max_node_tokens=400, num_q_heads=16, num_kv_heads=4)
+        _log(f"case wave items seed={seed} wave_kv={wave_kv} layout={layout} B={b.num_requests}")
+        (_, _), plan = parity(b, layout=layout, wave_kv_tokens=wave_kv, wave_max_tokens=100000)
+        st = plan.stats()
+        assert st.num_wave_items > 0 and st.num_workers > 0
+        assert list(st.tile_histogram)[2] > 0
+
+
+def test_wavefront_items_many_per_wavefront():
+    # far more items than the 8 x 4 wavefronts of four persistent workgroups: every wavefront walks a
+    # list of items, requesting the next item's rows while it finishes the current one
+    rng = np.random.default_rng(3)
+    lens = rng.integers(1, 700, 96)
+    b = wl.tree_batch([96], [lambda r, n: lens], num_q_heads=8, num_kv_heads=2, dtype="bf16", seed=53)
+    _log("case wave items, long lists")
+    (_, _), plan = parity(b, wave_kv_tokens=64, wave_max_tokens=100000, num_cus=4)
+    st = plan.stats()
+    assert st.num_workers == 4 and st.num_wave_items > 20 * 32
+
+
+@pytest.mark.parametrize("node_tokens", [64, 224, 240, 512])
+def test_tile_follows_the_kv_length_of_a_small_group(node_tokens):
+    # 5 requests x 4 heads = 20 rows: below the crossover the node runs as two 16-row blocks,
+    # from it on as one 64-row packed workgroup per KV head; same attention either way
+    _log(f"case 20 rows over {node_tokens} tokens")
+    b = wl.tree_batch([1, 5], [node_tokens, lambda rng, n: rng.integers(1, 40, n)],
+                      num_q_heads=8, num_kv_heads=2, dtype="bf16", seed=node_tokens)
+    (_, _), plan = parity(b, split_policy=pb.PAT_SPLIT_NONE)
+    ex = plan.export()
+    shared = [e for e in range(ex["num_entries"]) if ex["item_kv_len"][ex["entry_item"][e]] == node_tokens
+              and np.diff(ex["item_req_off"])[ex["entry_item"][e]] == 5]
+    tiles = sorted(int(ex["entry_tile"][e]) for e in shared)
+    assert tiles == ([1, 1] if node_tokens < 240 else [3])
+
+
 def test_debug_trace_records_every_workgroup():
     b = wl.config("C1")
     q, kp, vp, st = to_gpu(wl.make_tensors(b))
@@ -175,7 +218,7 @@ def test_debug_trace_records_every_workgroup():
         pb.pat_debug_set_trace(None)
     t = tr.cpu().numpy().reshape(n, 8)
     assert (t[:, 0] > 0).all() and (t[:, 1] >= t[:, 0]).all()
-    assert set((t[:, 3] >> 32).tolist()) <= {0, 1, 3, 4}
+    assert set((t[:, 3] >> 32).tolist()) <= {0, 1, 2, 3, 4}
     tr.zero_()
     pb.pat_forward(plan, q, kp, vp, st, b.softmax_scale, out, None, ws)     # switched off again
     torch.cuda.synchronize()
