@@ -123,6 +123,12 @@ typedef struct {
                                      /*   0 or negative = not used (the default: measured       */
                                      /*   slower than n = 128 on MI355X)                        */
     int32_t wave_max_tokens;         /* 0 = 4 * wave_kv_tokens                                  */
+    int32_t dual_launch;             /* forward as TWO kernels side by side (sec. "Multi-Stream */
+                                     /*   Forward"): packed tiles as 512-thread workgroups on   */
+                                     /*   the caller's stream, 16-row tiles as 256-thread       */
+                                     /*   workgroups (one KV head each, two per CU) on a stream */
+                                     /*   of the plan's own that forks from and joins the       */
+                                     /*   caller's.  1 = on, -1 = off, 0 = the planner decides  */
     int32_t reserved[1];             /* must be 0                                               */
 } pat_plan_opts;
 

@@ -18,6 +18,7 @@ int advance_plan(pat_plan_s &pl, const int32_t *new_kv_lens, const int32_t *bloc
 void refresh_view(pat_plan_s &pl);
 bool tile_available(int id);
 hipError_t launch_forward(int dtype, const FwdArgs &a, int n_entries, hipStream_t s);
+hipError_t launch_forward_stream(int dtype, const FwdArgs &a, int n_workgroups, hipStream_t s);
 hipError_t launch_merge(int dtype, const MergeArgs &a, hipStream_t s);
 }  // namespace pat
 
@@ -63,7 +64,15 @@ int pat_plan(const pat_batch_desc *batch, const pat_plan_opts *opts, pat_plan_t 
     return PAT_OK;
 }
 
-void pat_plan_destroy(pat_plan_t *plan) { delete plan; }
+void pat_plan_destroy(pat_plan_t *plan)
+{
+    if (!plan) return;
+    // the stream and events of a two-kernel launch (created by pat_plan_upload)
+    if (plan->ev_fork) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_fork));
+    if (plan->ev_join) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_join));
+    if (plan->side_stream) (void)hipStreamDestroy(static_cast<hipStream_t>(plan->side_stream));
+    delete plan;
+}
 
 // ---- planning on a worker thread ------------------------------------------------------------
 struct pat_plan_job_s {
@@ -188,6 +197,22 @@ int pat_plan_upload(pat_plan_t *plan, void *device_buf, size_t device_bytes, voi
     hipError_t e = hipMemcpyAsync(device_buf, plan->staging.data(), plan->layout.total,
                                   hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return PAT_ERR_HIP;
+    if (plan->dual && !plan->side_stream) {
+        // a stream of the plan's own (default priority) and the two events of the fork and join
+        hipStream_t st = nullptr;
+        hipEvent_t ef = nullptr, ej = nullptr;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&ef, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&ej, hipEventDisableTiming) != hipSuccess) {
+            if (ef) (void)hipEventDestroy(ef);
+            if (ej) (void)hipEventDestroy(ej);
+            if (st) (void)hipStreamDestroy(st);
+            return PAT_ERR_HIP;
+        }
+        plan->side_stream = st;
+        plan->ev_fork = ef;
+        plan->ev_join = ej;
+    }
     plan->device_buf = device_buf;
     return PAT_OK;
 }
@@ -259,6 +284,27 @@ int pat_forward(const pat_plan_t *plan, const void *q, const void *k_pool, const
     a.queue_ctr = reinterpret_cast<int32_t *>(const_cast<unsigned char *>(dev) + plan->layout.queue_ctr);
     a.workers = nullptr;
     a.wave_items = reinterpret_cast<const DevWaveItem *>(dev + plan->layout.wave_items);
+    a.unit_base = 0;
+    if (plan->dual) {
+        // packed tiles on the caller's stream, 16-row tiles on the plan's own, side by side
+        const int n_packed = plan->stream_begin, n_stream = (int)plan->units.size() - plan->stream_begin;
+        hipStream_t side = static_cast<hipStream_t>(plan->side_stream);
+        hipEvent_t fork = static_cast<hipEvent_t>(plan->ev_fork), join = static_cast<hipEvent_t>(plan->ev_join);
+        if (n_stream > 0 && n_packed > 0) {
+            if (hipEventRecord(fork, s) != hipSuccess || hipStreamWaitEvent(side, fork, 0) != hipSuccess)
+                return PAT_ERR_HIP;
+            if (launch_forward(plan->dtype, a, n_packed, s) != hipSuccess) return PAT_ERR_HIP;
+            a.unit_base = n_packed;
+            if (launch_forward_stream(plan->dtype, a, n_stream, side) != hipSuccess) return PAT_ERR_HIP;
+            if (hipEventRecord(join, side) != hipSuccess || hipStreamWaitEvent(s, join, 0) != hipSuccess)
+                return PAT_ERR_HIP;
+        } else if (n_stream > 0) {
+            if (launch_forward_stream(plan->dtype, a, n_stream, s) != hipSuccess) return PAT_ERR_HIP;
+        } else if (launch_forward(plan->dtype, a, n_packed, s) != hipSuccess) {
+            return PAT_ERR_HIP;
+        }
+        return PAT_OK;
+    }
     int n_workgroups = plan->queue_begin + plan->queue_workers;
     if (!plan->workers.empty()) {
         a.workers = reinterpret_cast<const DevWorker *>(dev + plan->layout.workers);

@@ -103,6 +103,7 @@ struct FwdArgs {
     int32_t queue_begin;          // units from here on are taken from a queue by persistent workgroups
     int32_t queue_workers;        // how many of those (the last workgroups of the grid); 0: no queue
     int32_t *queue_ctr;           // [0]: next queued unit, [1]: workers that have left; both 0 between launches
+    int32_t unit_base;            // unit of workgroup 0 (the 16-row kernel of a two-kernel launch)
     const DevWorker *workers;     // launches with wavefront items: one record per persistent workgroup
     const DevWaveItem *wave_items;
 };

@@ -117,6 +117,55 @@ __global__ __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(kVgprLimitAt
     }
 }
 
+// The 16-row tiles of a two-kernel launch (the paper's multi-stream forward, sec. "Multi-Stream
+// Forward": kernels of different tile configurations side by side on streams of their own).
+// A workgroup is 256 threads on ONE KV head with half a CU's registers, so two of them share a CU
+// and are scheduled independently: while one waits for its unit record, its first K/V stage or
+// its epilogue's stores, the other one streams.  (As halves of one 512-thread workgroup the two
+// heads start, wait and end together, and nothing is in flight during those phases.)
+template <typename T>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void forward_stream_kernel(
+    FwdArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kHalfSmemBytes];
+    const int u = a.unit_base + blockIdx.x;
+    unsigned long long t_start = 0;
+    if (a.trace) t_start = wall_clock64();
+    UnitRec ur;
+    unit_fetch(a.units + u, ur);
+    DevEntry ue;
+    ue.req_off = ur.req_off();
+    ue.n_req = ur.n_req();
+    ue.page_off = ur.page_off();
+    ue.n_pages = ur.n_pages();
+    ue.kv_len = ur.kv_len();
+    ue.row_begin = ur.row_begin();
+    ue.n_rows = ur.n_rows();
+    ue.tile = ur.tile();
+    if (ue.tile == TILE_STREAM16)
+        tile_stream16<T>(a, ue, ur, u, ur.kvh0(), true, threadIdx.x, smem);
+    else
+        tile_valu16<T>(a, ue, ur.kvh0(), true, threadIdx.x, smem);
+    if (a.trace && threadIdx.x == 0) {
+        unsigned long long *rec = a.trace + 8ull * u;
+        rec[0] = t_start;
+        rec[1] = wall_clock64();
+        rec[2] = ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |
+                 (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);      // XCC_ID, HW_ID
+        rec[3] = ((unsigned long long)ue.tile << 32) | (unsigned)ue.kv_len;
+    }
+}
+
+hipError_t launch_forward_stream(int dtype, const FwdArgs &a, int n_workgroups, hipStream_t s)
+{
+    if (n_workgroups == 0) return hipSuccess;
+    FwdArgs args = a;
+    void *params[] = {&args};
+    const void *fn = dtype == PAT_F16 ? (const void *)forward_stream_kernel<F16>
+                                      : (const void *)forward_stream_kernel<BF16>;
+    return hipLaunchKernel(fn, dim3((unsigned)n_workgroups), dim3(256), params, 0, s);
+}
+
 // Launches that hold wavefront items (TILE_WAVE16): as many persistent workgroups as the planner
 // made lists for.  A workgroup first runs its workgroup-level units (packed tiles, long 16-row
 // streams) one after the other, then its eight wavefronts part ways, each walking its own list of

@@ -129,6 +129,12 @@ struct pat_plan_s {
     // Units [queue_begin, units.size()) are 16-row units taken from a queue by queue_workers
     // persistent workgroups; queue_begin == units.size(): every unit is a workgroup of its own.
     int32_t queue_begin = 0, queue_workers = 0;
+    // Two-kernel launches: units [0, stream_begin) are packed tiles (512-thread workgroups on the
+    // caller's stream), units [stream_begin, units.size()) 16-row tiles of one KV head each
+    // (256-thread workgroups on side_stream, which forks from and joins the caller's stream).
+    bool dual = false;
+    int32_t stream_begin = 0;
+    void *side_stream = nullptr, *ev_fork = nullptr, *ev_join = nullptr;   // created by pat_plan_upload
     // Launches with wavefront items run as `workers.size()` persistent workgroups instead.
     std::vector<pat::DevWorker> workers;
     std::vector<pat::DevWaveItem> wave_items;

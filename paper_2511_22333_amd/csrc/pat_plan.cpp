@@ -442,6 +442,8 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     const int64_t c0q = c0p * 73 / 100, c1q = std::max<int64_t>(1, c1p * 90 / 100);
     const int64_t c0s = own_model ? o.model_ns[2] : 4000, c1s = own_model ? o.model_ns[3] : 20;
     const int64_t c0w = 1500, c1w = 8 * c1s;
+    // Two-kernel launch: 16-row tiles as 256-thread workgroups of one KV head, two per CU.
+    const bool dual = o.dual_launch > 0 && o.force_tile != TILE_WAVE16 && !(o.wave_kv_tokens > 0);
     // TILE_WAVE16 (n = 32, one wavefront per item): where 16-row packs of a launch of many rounds
     // are short.  wave_kv = longest item, wave_max = longest pack that is cut into such items.
     int32_t wave_kv = 0, wave_max = 0;
@@ -590,19 +592,21 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
             }
             const int64_t floor_bound = std::max(c0p, c0s) + 2000;
             int64_t bound;
-            bool single_heads = true;
-            if (workgroups(floor_bound, true) <= slots) {
+            // (two-kernel launches: a 16-row workgroup holds one KV head and half a CU; two of them
+            // are counted as one workgroup of two heads)
+            const bool single_heads = !dual;
+            if (workgroups(floor_bound, single_heads) <= slots) {
                 bound = floor_bound;
             } else {
                 int64_t lo = floor_bound, hi = std::max(longest, floor_bound + 1);   // W(hi) minimal
-                if (workgroups(hi, true) > slots) {
+                if (workgroups(hi, single_heads) > slots) {
                     for (size_t i = 0; i < packs.size(); ++i)
                         cuts[i] = Cut{parts_for(packs[i], std::max<int64_t>(256, share), 1), 2};
                     break;                                          // cannot fit one round anyway
                 }
                 while (lo + 1 < hi) {                               // W(lo) > slots >= W(hi)
                     const int64_t mid = (lo + hi) / 2;
-                    if (workgroups(mid, true) <= slots) hi = mid; else lo = mid;
+                    if (workgroups(mid, single_heads) <= slots) hi = mid; else lo = mid;
                 }
                 bound = hi;
             }
@@ -730,7 +734,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     // launch order: longest-running first, priced as the cuts were (bytes; a packed workgroup
     // a quarter above its bytes)
     auto heads_of = [&](const E &x) {
-        return is_packed_tile(x.tile) || x.tile == TILE_WAVE16 ? 1 : item_heads[x.item];
+        return is_packed_tile(x.tile) || x.tile == TILE_WAVE16 || dual ? 1 : item_heads[x.item];
     };
     auto cost = [&](const E &x) {
         const int64_t len = pl.item_kv_len[x.item];
@@ -738,6 +742,8 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     };
     std::stable_sort(es.begin(), es.end(),
                      [&](const E &a, const E &c) { return cost(a) > cost(c); });
+    if (dual)       // the packed tiles' kernel takes the first units, the 16-row kernel the rest
+        std::stable_partition(es.begin(), es.end(), [&](const E &x) { return is_packed_tile(x.tile); });
     std::memset(&pl.stats, 0, sizeof pl.stats);
     std::vector<int32_t> unit_item, wave_item_of;       // the item of every unit / wavefront item
     for (const E &e : es) {
@@ -795,8 +801,14 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     }
     pl.queue_begin = (int32_t)pl.units.size();
     pl.queue_workers = 0;
+    pl.dual = dual;
+    pl.stream_begin = 0;
+    while (pl.stream_begin < (int32_t)pl.units.size() && is_packed_tile(pl.units[pl.stream_begin].e.tile))
+        ++pl.stream_begin;
     const int32_t cus = o.num_cus > 0 ? o.num_cus : 256;
-    if (!pl.wave_items.empty()) {
+    if (dual) {
+        // no queue: the hardware hands the 16-row workgroups to half CUs as they free up
+    } else if (!pl.wave_items.empty()) {
         // Static schedule of a launch with wavefront items: `cus` persistent workgroups.  The
         // workgroup-level units go to the workgroup that is free first, longest first, by the
         // run-time model; then the wavefront items go, longest first, to the wavefront that is

@@ -201,6 +201,44 @@ def test_tile_follows_the_kv_length_of_a_small_group(node_tokens):
     assert tiles == ([1, 1] if node_tokens < 240 else [3])
 
 
+@pytest.mark.parametrize("layout", ["NHD", "HND"])
+def test_two_kernel_launch_on_forests_and_in_a_graph(layout):
+    # dual_launch: packed tiles as 512-thread workgroups on the caller's stream, 16-row tiles as
+    # 256-thread workgroups of one KV head on the plan's own stream, forked from and joined to the
+    # caller's (sec. "Multi-Stream Forward"); eagerly, and captured in a HIP graph that is replayed
+    # three times with eager work in between
+    for seed in (1, 2, 6):
+        b = wl.random_forest_batch(seed, dtype="bf16" if seed % 2 else "fp16", max_requests=30,
+                                   max_node_tokens=300, num_q_heads=16, num_kv_heads=4,
+                                   duplicate_rows=(seed % 3 == 0))
+        _log(f"case two kernels seed={seed} layout={layout} B={b.num_requests}")
+        cpu = wl.make_tensors(b, poison=True, layout=layout)
+        want, want_lse = run_oracle(b, cpu)
+        q, kp, vp, st = to_gpu(cpu)
+        plan = pb.plan_for_batch(b, dual_launch=1)
+        dev, ws = pb.alloc_plan_buffers(plan)
+        pb.pat_plan_upload(plan, dev)
+        out = torch.full_like(q, float("nan"))
+        lse = torch.full((b.num_requests, b.num_q_heads), float("nan"), dtype=torch.float32, device="cuda")
+        pb.pat_decode_attention(plan, q, kp, vp, st, b.softmax_scale, out, lse, ws)
+        torch.cuda.synchronize()
+        compare(b, out, lse, want, want_lse)
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            pb.pat_decode_attention(plan, q, kp, vp, st, b.softmax_scale, out, lse, ws)
+        for _ in range(3):
+            out.fill_(float("nan"))
+            lse.fill_(float("nan"))
+            ws.fill_(0xFF)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            compare(b, out, lse, want, want_lse)
+
+
 def test_debug_trace_records_every_workgroup():
     b = wl.config("C1")
     q, kp, vp, st = to_gpu(wl.make_tensors(b))
