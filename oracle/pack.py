@@ -180,10 +180,6 @@ def model_cost(packs: Sequence[Pack], d: int = 1) -> int:
     return sum(p.kv_len * d + 4 * len(p.queries) * d for p in packs)
 
 
-def one_query_per_cta_cost(kv_lens: Sequence[int], d: int = 1) -> int:
-    return sum(int(n) * d + 4 * d for n in kv_lens)
-
-
 def long_kv_split(packs: Sequence[Pack], kv_lens: Sequence[int], P: int) -> List[Pack]:
     """Cut every pack longer than the mean pack length into equal page-aligned parts."""
     if not packs:
