@@ -129,6 +129,9 @@ typedef struct {
                                      /*   workgroups (one KV head each, two per CU) on a stream */
                                      /*   of the plan's own that forks from and joins the       */
                                      /*   caller's.  1 = on, -1 = off, 0 = the planner decides  */
+    int32_t packed_min_tokens;       /* 17..32 rows over fewer tokens than this run as two      */
+                                     /*   16-row blocks, not as one 64-row packed workgroup;    */
+                                     /*   0 = the built-in MI355X crossover (48)                */
     int32_t reserved[1];             /* must be 0                                               */
 } pat_plan_opts;
 

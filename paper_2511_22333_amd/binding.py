@@ -54,7 +54,7 @@ class pat_plan_opts(C.Structure):
                 ("num_cus", C.c_int32), ("tail_reserve_pages", C.c_int32),
                 ("model_ns", C.c_int32 * 4), ("wave_kv_tokens", C.c_int32),
                 ("wave_max_tokens", C.c_int32), ("dual_launch", C.c_int32),
-                ("reserved", C.c_int32 * 1)]
+                ("packed_min_tokens", C.c_int32), ("reserved", C.c_int32 * 1)]
 
 
 class pat_plan_stats(C.Structure):
@@ -200,7 +200,8 @@ def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, page_size: int, n
              merge_factor: int = 0, split_policy: int = PAT_SPLIT_AUTO,
              split_target_tokens: int = 0, force_tile: int = -1, num_cus: int = 0,
              tail_reserve_pages: int = 0, model_ns=None, wave_kv_tokens: int = 0,
-             wave_max_tokens: int = 0, dual_launch: int = 0, background: bool = False, node_parent: Optional[np.ndarray] = None,
+             wave_max_tokens: int = 0, dual_launch: int = 0, packed_min_tokens: int = 0,
+             background: bool = False, node_parent: Optional[np.ndarray] = None,
              node_num_pages: Optional[np.ndarray] = None,
              req_leaf_node: Optional[np.ndarray] = None) -> Plan:
     bt = np.ascontiguousarray(block_tables, dtype=np.int32)
@@ -226,6 +227,7 @@ def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, page_size: int, n
     o.tail_reserve_pages = int(tail_reserve_pages)
     o.wave_kv_tokens, o.wave_max_tokens = int(wave_kv_tokens), int(wave_max_tokens)
     o.dual_launch = int(dual_launch)
+    o.packed_min_tokens = int(packed_min_tokens)
     if model_ns is not None:
         for i, x in enumerate(model_ns):
             o.model_ns[i] = int(x)

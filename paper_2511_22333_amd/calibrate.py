@@ -1,4 +1,14 @@
-"""Calibration of the planner's run-time model on the GPU at hand.
+"""Offline derivation of the tile family and of the planner's constants on the GPU at hand
+(sec. "Multi-tile Kernel": latency-versus-size microbenchmark, constraints on feasible tiles,
+kernel-equivalence run, KV-length decision; sec. "Tile Selection").
+
+    python -m paper_2511_22333_amd.calibrate latency       # L and B of the memory system
+    python -m paper_2511_22333_amd.calibrate solver        # feasible (m, n) under the constraints
+    python -m paper_2511_22333_amd.calibrate equivalence   # every tile on a no-prefix batch, KV 1024
+    python -m paper_2511_22333_amd.calibrate sweep-kv      # KV-length thresholds of the selector
+    python -m paper_2511_22333_amd.calibrate model         # run-time model of the split (default)
+
+The run-time model:
 
 The device-aware split (PAT_SPLIT_AUTO) balances one-round batches with a linear model of a
 workgroup's run time: packed workgroup = a + b * tokens, 16-row workgroup = c + d * tokens *
@@ -89,9 +99,146 @@ def fit(rows):
     return res
 
 
-def main():
-    if not torch.cuda.is_available():
-        sys.exit("calibrate: needs the GPU")
+# ---- latency versus request size (the paper's Fig. 5a on this GPU) -----------------------------
+def latency_curve(workgroups=(1, 256), loads=(1, 2, 4, 8, 16, 32), buffer_bytes=2 << 30, iters=64):
+    """For every number of concurrent workgroups: [(request bytes, ns per request)], and the fit
+    ns = L + bytes / B of the curve's ends (flat part = latency L, slope = 1 / bandwidth B per
+    workgroup)."""
+    from . import probe
+    buf = torch.empty(buffer_bytes, dtype=torch.uint8, device="cuda")
+    buf.fill_(1)
+    out = {}
+    for w in workgroups:
+        pts = [(4096 * k, probe.request_latency_ns(buf, loads_per_thread=k, workgroups=w, iters=iters))
+               for k in loads]
+        x = np.array([p[0] for p in pts], float)
+        y = np.array([p[1] for p in pts], float)
+        (c0, c1), *_ = np.linalg.lstsq(np.stack([np.ones_like(x), x], 1), y, rcond=None)
+        out[w] = {"points": pts, "latency_ns": float(c0),
+                  "gbps_per_workgroup": float(1.0 / c1) if c1 > 0 else float("inf"),
+                  "gbps_all": float(w / c1) if c1 > 0 else float("inf")}
+    return out
+
+
+# ---- feasible tiles under the hardware's constraints (the paper's constraints 1-3, restated) ----
+CU = {"lds_bytes": 160 * 1024, "vgprs_per_simd": 512, "simds": 4, "cus": 256, "lane_bytes": 4}
+
+
+def tile_solver(latency_ns=2500.0, hbm_gbps=6900.0, head_dim=128, elem=2, stages=2):
+    """Feasible (m, n) for a 512-thread workgroup that owns a CU, m = query rows, n = KV tokens per
+    pipeline stage, powers of two from 16:
+      (1) LDS: `stages` staged K tiles (n x 272 B padded rows) and V^T tiles (128 x (2 n + 16) B) fit
+          the CU's LDS -- only packed tiles (m > 16) stage V; 16-row tiles keep K per wavefront;
+      (2) memory: the loads a CU keeps in flight, stages x n x 2 (K, V) x head_dim x elem, cover its
+          share of latency x bandwidth (else the tile is latency-bound, however fast it computes);
+      (3) registers: fp32 accumulators O[m x head_dim] and S[m x n / 2] (two token halves) spread over
+          the workgroup's 512 lanes, plus Q operands and the in-flight ring, fit 256 VGPRs a lane.
+    Returns a list of dicts, one per (m, n), with the three verdicts."""
+    need_in_flight = latency_ns * 1e-9 * hbm_gbps * 1e9 / CU["cus"]           # bytes per CU
+    out = []
+    for m in (16, 32, 64, 128, 256):
+        for n in (16, 32, 64, 128, 256):
+            kv_stage = n * 2 * head_dim * elem
+            if m <= 16:
+                # eight wavefront streams per CU whatever n is: n / 32 of them work on one KV head
+                # (n = 32: one wavefront per item, n = 128: four per head, two heads per workgroup);
+                # a wavefront's stage is min(n, 32) tokens, its current and next stage are in flight
+                w = min(n, 32)
+                lds = 8 * w * (head_dim * elem + 16)
+                in_flight = 8 * 2 * w * 2 * head_dim * elem
+                acc = 16 * head_dim // 64 + 8 + 16 + 64 + 32   # O, S, Q, K/V load buffers, V copy
+            else:
+                lds = stages * (n * (head_dim * elem + 16) + head_dim * (n * elem + 16))
+                in_flight = stages * kv_stage
+                rows_per_wave = max(32, m // 4)
+                acc = rows_per_wave * head_dim // 64 + rows_per_wave * (n // 2) // 64 \
+                    + rows_per_wave * head_dim * elem // (64 * 4) + stages * kv_stage // (512 * 4) + 48
+            out.append({"m": m, "n": n, "lds_bytes": lds, "lds_ok": lds <= CU["lds_bytes"],
+                        "in_flight_bytes": in_flight, "memory_ok": in_flight >= 0.95 * need_in_flight,
+                        "vgprs": acc, "registers_ok": acc <= 256,
+                        "feasible": lds <= CU["lds_bytes"] and in_flight >= 0.95 * need_in_flight and acc <= 256})
+    return out, need_in_flight
+
+
+def built_tiles():
+    out = []
+    for t in range(pb.lib.pat_num_tiles()):
+        rc, m, n = pb.pat_tile_info(t)
+        if rc == pb.PAT_OK:
+            out.append((t, m, n))
+    return out
+
+
+# ---- kernel-equivalence run (the paper's Fig. 5c-d / Fig. 6 on this GPU) -------------------------
+def _time_forward(batch, copies, launches=20, replays=3, **plan_kw):
+    plan = pb.plan_for_batch(batch, **plan_kw)
+    dev, ws = pb.alloc_plan_buffers(plan)
+    pb.pat_plan_upload(plan, dev)
+    out = torch.empty_like(copies[0][0])
+    lse = torch.empty(batch.num_requests, batch.num_q_heads, dtype=torch.float32, device="cuda")
+    R = len(copies)
+
+    def fwd(i):
+        q, kp, vp, st = copies[i % R]
+        pb.pat_decode_attention(plan, q, kp, vp, st, batch.softmax_scale, out, lse, ws)
+
+    for i in range(3):
+        fwd(i)
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(replays):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(launches):
+            fwd(i)
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b) * 1e3 / launches)
+    return times, out, lse, plan
+
+
+def kernel_equivalence(batch_size=512, kv_len=1024, num_q_heads=32, num_kv_heads=8, copies=2):
+    """Every tile of the family on the SAME batch without any shared prefix (batch a multiple of the
+    CU count, every request kv_len tokens): {tile id: (m, n, us min, us max, GB/s)} and the batch."""
+    lens = np.full(batch_size, kv_len)
+    b = wl.tree_batch([batch_size], [lambda rng, n: lens], num_q_heads=num_q_heads,
+                      num_kv_heads=num_kv_heads, dtype="bf16", seed=7100, name="equivalence")
+    tensors = [wl.make_tensors(b, seed=7100 + i, device="cuda") for i in range(copies)]
+    res = {}
+    for t, m, n in built_tiles():
+        if m == 16 and n == 4 and batch_size * kv_len > (1 << 18):
+            continue                                     # the VALU cross-check tile: small runs only
+        times, out, lse, plan = _time_forward(b, tensors, force_tile=t)
+        res[t] = {"m": m, "n": n, "us_min": min(times), "us_max": max(times),
+                  "gbps": b.unique_kv_bytes() / min(times) / 1e3}
+    return res, b, tensors
+
+
+# ---- KV-length thresholds of the tile selector -------------------------------------------------
+def sweep_kv(kv_lens=(16, 32, 48, 64, 96, 128, 192, 256, 384, 512, 1024), groups=256):
+    """(a) 20 query rows (5 requests x GQA 4) over a shared node of kv tokens: one 64-row packed
+    workgroup per KV head against two 16-row blocks; (b) unshared requests of kv tokens: the n = 128
+    tile (four wavefronts per KV head) against the n = 32 tile (one wavefront per KV head).
+    Returns two lists of (kv, us first option, us second option)."""
+    shared, leaves = [], []
+    for kv in kv_lens:
+        b = wl.tree_batch([groups, groups * 5], [kv, 16], num_q_heads=32, num_kv_heads=8, dtype="bf16",
+                          seed=7200 + kv, name=f"sweep{kv}")
+        t = [wl.make_tensors(b, seed=i, device="cuda") for i in range(2)]
+        packed, *_ = _time_forward(b, t, packed_min_tokens=1, split_policy=pb.PAT_SPLIT_NONE)
+        blocks, *_ = _time_forward(b, t, packed_min_tokens=1 << 30, split_policy=pb.PAT_SPLIT_NONE)
+        shared.append((kv, min(packed), min(blocks)))
+        lens = np.full(groups * 8, kv)
+        b = wl.tree_batch([groups * 8], [lambda rng, n: lens], num_q_heads=32, num_kv_heads=8, dtype="bf16",
+                          seed=7300 + kv, name=f"leaf{kv}")
+        t = [wl.make_tensors(b, seed=i, device="cuda") for i in range(2)]
+        n128, *_ = _time_forward(b, t, split_policy=pb.PAT_SPLIT_NONE)
+        n32, *_ = _time_forward(b, t, split_policy=pb.PAT_SPLIT_NONE, wave_kv_tokens=1 << 20)
+        leaves.append((kv, min(n128), min(n32)))
+    return shared, leaves
+
+
+def run_model():
     rows = []
     for b in _one_round_batches():
         rows += workgroup_times(b)
@@ -114,6 +261,43 @@ def main():
         if res[64]:
             out["ratio_64_row_tile"] = [round(res[64][0] / res[128][0], 2), round(res[64][1] / res[128][1], 2)]
         print(json.dumps(out))
+
+
+def main(argv=None):
+    argv = sys.argv[1:] if argv is None else argv
+    what = argv[0] if argv else "model"
+    if what == "solver":
+        tiles, need = tile_solver()
+        built = {(m, n) for _, m, n in built_tiles()}
+        print(f"bytes a CU must keep in flight: {need / 1024:.0f} KiB (latency x bandwidth / CUs)")
+        print("   m    n   LDS KiB  in flight KiB  VGPRs  feasible  built")
+        for t in tiles:
+            print(f"{t['m']:4d} {t['n']:4d} {t['lds_bytes'] / 1024:8.1f} {t['in_flight_bytes'] / 1024:13.0f} "
+                  f"{t['vgprs']:6d}  {'yes' if t['feasible'] else 'no ':8s} {'*' if (t['m'], t['n']) in built else ''}")
+        return
+    if not torch.cuda.is_available():
+        sys.exit("calibrate: needs the GPU")
+    if what == "latency":
+        for w, r in latency_curve().items():
+            print(f"{w} workgroups at once: " + ", ".join(f"{b >> 10} KiB {ns:.0f} ns" for b, ns in r["points"]))
+            print(f"   fit: latency {r['latency_ns']:.0f} ns, {r['gbps_per_workgroup']:.1f} GB/s per workgroup, "
+                  f"{r['gbps_all']:.0f} GB/s in all")
+    elif what == "equivalence":
+        res, b, _ = kernel_equivalence()
+        print(f"no shared prefix: {b.num_requests} requests x 1024 tokens, {b.unique_kv_bytes() / 1e6:.0f} MB")
+        for t, r in res.items():
+            print(f"tile {t} (m = {r['m']}, n = {r['n']}): {r['us_min']:.1f} .. {r['us_max']:.1f} us/step, "
+                  f"{r['gbps']:.0f} GB/s")
+    elif what == "sweep-kv":
+        shared, leaves = sweep_kv()
+        print("20 rows over a shared node:   kv   64-row packed   two 16-row blocks   (us/step)")
+        for kv, a, c in shared:
+            print(f"{kv:34d} {a:14.1f} {c:19.1f}   {'packed' if a < c else 'blocks'}")
+        print("unshared requests:            kv   n = 128 (4 wavefronts)   n = 32 (1 wavefront)")
+        for kv, a, c in leaves:
+            print(f"{kv:34d} {a:22.1f} {c:22.1f}   {'n=128' if a < c else 'n=32'}")
+    else:
+        run_model()
 
 
 if __name__ == "__main__":

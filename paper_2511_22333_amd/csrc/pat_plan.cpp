@@ -351,10 +351,10 @@ int validate(const pat_batch_desc &b)
 //   n: the 16-row family has two KV tiles: n = 32 (TILE_WAVE16, one wavefront per item) for
 //      entries of up to `wave_kv` tokens where the launch runs many rounds (wave_kv = 0: never),
 //      n = 128 (TILE_STREAM16, four wavefronts per KV head) otherwise.
-constexpr int32_t kPackedMinTokens = 240;
-int32_t select_tile(int32_t rows, int32_t kv_len, int32_t wave_kv)
+constexpr int32_t kPackedMinTokens = 48;
+int32_t select_tile(int32_t rows, int32_t kv_len, int32_t wave_kv, int32_t packed_min)
 {
-    if (rows <= 16 || (rows <= 32 && kv_len < kPackedMinTokens)) {
+    if (rows <= 16 || (rows <= 32 && kv_len < packed_min)) {
         if (wave_kv > 0 && kv_len <= wave_kv && g_tile_available[TILE_WAVE16]) return TILE_WAVE16;
         if (g_tile_available[TILE_STREAM16]) return TILE_STREAM16;
     }
@@ -383,7 +383,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
         return PAT_ERR_INVALID_ARG;
     if (o.split_policy == PAT_SPLIT_TARGET && o.split_target_tokens < 1)
         return PAT_ERR_INVALID_ARG;
-    if (o.merge_factor < 0 || o.num_cus < 0) return PAT_ERR_INVALID_ARG;
+    if (o.merge_factor < 0 || o.num_cus < 0 || o.packed_min_tokens < 0) return PAT_ERR_INVALID_ARG;
     if (o.force_tile < -1 || o.force_tile >= NUM_TILES) return PAT_ERR_INVALID_ARG;
     if (o.force_tile >= 0 && !g_tile_available[o.force_tile]) return PAT_ERR_UNSUPPORTED;
     for (int32_t x : o.reserved)
@@ -442,6 +442,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     const int64_t c0q = c0p * 73 / 100, c1q = std::max<int64_t>(1, c1p * 90 / 100);
     const int64_t c0s = own_model ? o.model_ns[2] : 4000, c1s = own_model ? o.model_ns[3] : 20;
     const int64_t c0w = 1500, c1w = 8 * c1s;
+    const int32_t packed_min = o.packed_min_tokens > 0 ? o.packed_min_tokens : kPackedMinTokens;
     // Two-kernel launch: 16-row tiles as 256-thread workgroups of one KV head, two per CU.
     const bool dual = o.dual_launch > 0 && o.force_tile != TILE_WAVE16 && !(o.wave_kv_tokens > 0);
     // TILE_WAVE16 (n = 32, one wavefront per item): where 16-row packs of a launch of many rounds
@@ -452,14 +453,20 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     } else if (o.force_tile < 0 && o.wave_kv_tokens >= 0 && g_tile_available[TILE_WAVE16]) {
         const bool many_rounds = (unique_tokens * b.num_kv_heads + (o.num_cus > 0 ? o.num_cus : 256) - 1) /
                                  (o.num_cus > 0 ? o.num_cus : 256) > 1024;
-        // Measured on MI355X (C3, C4 and a KV-length sweep): with items of 128..512 tokens the
-        // n = 32 tile is 3..20 % slower than the n = 128 tile on these batches -- the streams of
-        // eight independent wavefronts per CU crowd the packed tiles' loads out of the memory
-        // system.  So it is used where the caller asks for it, not by default.
-        (void)many_rounds;
+        // Measured on MI355X (the calibration module's KV-length sweep, C3, C4): on a batch of
+        // nothing but short unshared requests the n = 32 tile beats the n = 128 tile up to about
+        // 384 tokens (by 36 % at 64 tokens, 21 % at 128, 7 % at 256); next to packed tiles or long
+        // streams it does not (C3, C4: equal to 20 % slower -- eight independent streams per CU
+        // crowd the packed tiles' loads out, and the static lists start behind the units).  So the
+        // planner picks it only for launches of many rounds in which EVERY pack is such a request.
+        bool all_short = many_rounds && o.split_policy == PAT_SPLIT_AUTO && o.wave_kv_tokens == 0;
+        for (size_t i = 0; i < packs.size() && all_short; ++i)
+            all_short = (int64_t)packs[i].reqs.size() * G <= 16 && packs[i].kv_len <= 384;
         if (o.wave_kv_tokens > 0) {
             wave_kv = o.wave_kv_tokens;
             wave_max = o.wave_max_tokens > 0 ? o.wave_max_tokens : 4 * wave_kv;
+        } else if (all_short) {
+            wave_kv = wave_max = 384;
         }
     }
     {
@@ -502,7 +509,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
             auto packed_c1 = [&](const Pack &p) { return (int64_t)p.reqs.size() * G <= 64 ? c1q : c1p; };
             auto is_packed = [&](const Pack &p) {
                 const int64_t rows = (int64_t)p.reqs.size() * G;
-                return rows > 32 || (rows > 16 && p.kv_len >= kPackedMinTokens);
+                return rows > 32 || (rows > 16 && p.kv_len >= packed_min);
             };
             auto is_wave = [&](const Pack &p) { return !is_packed(p) && wave_kv > 0 && p.kv_len <= wave_max; };
             // bound = run time in ns a workgroup may take
@@ -618,7 +625,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
             for (size_t i = 0; i < packs.size(); ++i) {
                 const Pack &p = packs[i];
                 const int64_t rows = (int64_t)p.reqs.size() * G;
-                const bool packed = rows > 32 || (rows > 16 && p.kv_len >= kPackedMinTokens);
+                const bool packed = rows > 32 || (rows > 16 && p.kv_len >= packed_min);
                 if (cuts[i].wave || o.force_tile == TILE_WAVE16) {
                     cuts[i].wave = true;
                 } else if (!packed && p.kv_len <= wave_max && o.wave_kv_tokens > 0) {
@@ -719,13 +726,13 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
         int32_t rows = n_req * G;
         const int32_t len = pl.item_kv_len[k];
         const int32_t wkv = item_wave[k] ? INT32_MAX : 0;
-        int32_t tile = o.force_tile >= 0 ? o.force_tile : select_tile(rows, len, wkv);
+        int32_t tile = o.force_tile >= 0 ? o.force_tile : select_tile(rows, len, wkv, packed_min);
         int32_t m = kTiles[tile].m;
         int32_t blocks = (rows + m - 1) / m;
         int32_t per = (rows + blocks - 1) / blocks;
         if (o.force_tile < 0 && blocks > 1 && is_packed_tile(tile)) {
             // equal blocks may fit a smaller tile than the largest one
-            int32_t t2 = select_tile(per, len, 0);
+            int32_t t2 = select_tile(per, len, 0, packed_min);
             if (is_packed_tile(t2) && kTiles[t2].m >= per) { tile = t2; m = kTiles[t2].m; }
         }
         for (int32_t rb = 0; rb < rows; rb += per)

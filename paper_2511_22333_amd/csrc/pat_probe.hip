@@ -40,14 +40,15 @@ __global__ __launch_bounds__(512) void read_kernel(const u32x4 *base, size_t per
 // per thread (256 * 16 * LOADS bytes, contiguous), waits until all of them are there, and does that
 // `iters` times on fresh addresses.  Reports the mean time of one such request in nanoseconds.
 template <int LOADS>
-__global__ __launch_bounds__(256) void latency_kernel(const u32x4 *p, size_t n_vec, int iters,
+__global__ __launch_bounds__(256) void latency_kernel(const u32x4 *p, size_t n_vec, int iters, int seed,
                                                       float *ns_out, uint32_t *sink)
 {
     const size_t chunk = (size_t)256 * LOADS;                     // vectors per request
     const size_t n_chunks = n_vec / chunk;
     u32x4 acc = {0u, 0u, 0u, 0u};
     // a different chunk per (iteration, workgroup), spread over the whole buffer
-    size_t c = ((size_t)blockIdx.x * 2654435761u) % n_chunks;
+    // (`seed` moves every workgroup's walk: a second launch must not find the first one's lines cached)
+    size_t c = ((size_t)blockIdx.x * 2654435761u + (size_t)seed * 40503u) % n_chunks;
     __syncthreads();
     const unsigned long long t0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
@@ -92,17 +93,18 @@ int pat_probe_read(const void *buf, size_t bytes, int nontemporal, int workgroup
 }
 
 // `workgroups` workgroups each make `iters` dependent requests of 256 * 16 * loads_per_thread bytes
-// (loads_per_thread in {1, 2, 4, 8, 16, 32}) from `buf` (`bytes` long, at least 64 requests);
+// (loads_per_thread in {1, 2, 4, 8, 16, 32}) from `buf` (`bytes` long, at least 64 requests), the
+// walk through the buffer starting at a place that depends on `seed`;
 // ns_out[workgroup] (device floats) receives the mean time per request.
 int pat_probe_latency(const void *buf, size_t bytes, int loads_per_thread, int workgroups, int iters,
-                      float *ns_out, void *sink, void *stream)
+                      int seed, float *ns_out, void *sink, void *stream)
 {
     if (!buf || !sink || !ns_out || workgroups < 1 || iters < 1) return -1;
     const u32x4 *p = static_cast<const u32x4 *>(buf);
     size_t n = bytes / 16;
     if (n < (size_t)64 * 256 * loads_per_thread) return -1;
     uint32_t *s = static_cast<uint32_t *>(sink);
-    void *params[] = {&p, &n, &iters, &ns_out, &s};
+    void *params[] = {&p, &n, &iters, &seed, &ns_out, &s};
     const void *fn;
     switch (loads_per_thread) {
     case 1: fn = (const void *)latency_kernel<1>; break;

@@ -17,8 +17,8 @@ lib = C.CDLL(LIB_PATH)
 lib.pat_probe_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p,
                                C.POINTER(C.c_size_t), C.c_void_p]
 lib.pat_probe_read.restype = C.c_int
-lib.pat_probe_latency.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_void_p,
-                                  C.c_void_p, C.c_void_p]
+lib.pat_probe_latency.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_int,
+                                  C.c_void_p, C.c_void_p, C.c_void_p]
 lib.pat_probe_latency.restype = C.c_int
 
 
@@ -64,9 +64,9 @@ def request_latency_ns(buf, *, loads_per_thread, workgroups, iters=64):
     `workgroups` workgroups making such requests at the same time."""
     ns = torch.zeros(workgroups, dtype=torch.float32, device=buf.device)
     sink = torch.zeros(4, dtype=torch.uint8, device=buf.device)
-    for _ in range(2):                               # the first launch warms the TLBs
+    for seed in range(2):                            # the first launch warms up; other addresses each time
         rc = lib.pat_probe_latency(buf.data_ptr(), buf.numel(), loads_per_thread, workgroups, iters,
-                                   ns.data_ptr(), sink.data_ptr(), _stream())
+                                   seed + 1, ns.data_ptr(), sink.data_ptr(), _stream())
         if rc != 0:
             raise RuntimeError(f"pat_probe_latency failed ({rc})")
         torch.cuda.synchronize()

@@ -8,6 +8,12 @@ from paper_2511_22333_amd import binding as pb
 from paper_2511_22333_amd import workloads as wl
 
 TOL = {"fp16": 2e-3, "bf16": 1e-2}      # max-abs error of out against the fp64 oracle
+# ... except where the output's own 16-bit rounding is coarser than that: half a unit in the last
+# place is |x| * 2^-9 (bf16, 8 significant bits) or |x| * 2^-12 (fp16).  Three of them are allowed
+# for outputs that large (one for the softmax weights, which are rounded to the element type
+# before the second product and do not average out over two or three tokens, one for the output's
+# own rounding, one for everything in fp32); that exceeds the absolute bound from |x| = 1.7 (bf16) on
+HALF_ULP = {"fp16": 2.0 ** -12, "bf16": 2.0 ** -9}
 # lse: the scores are fp32 sums of exact 16-bit products and the sum of exponentials is fp32, so
 # the error is a few fp32 roundings of the score itself: 1e-4 absolute up to |lse| = 32, and in
 # proportion beyond (keys made 30-40 times louder push |lse| into the hundreds)
@@ -55,8 +61,10 @@ def compare(batch, out, lse, want, want_lse, req_ids=None):
     if req_ids is not None:
         got = got[np.asarray(req_ids)]
     assert np.isfinite(got).all(), "non-finite output (poison leaked or partial unwritten)"
-    err = np.abs(got - want).max()
-    assert err <= TOL[batch.dtype], f"max-abs error {err} > {TOL[batch.dtype]}"
+    diff = np.abs(got - want)
+    err = diff.max()
+    tol = np.maximum(TOL[batch.dtype], 3 * HALF_ULP[batch.dtype] * np.abs(want))
+    assert (diff <= tol).all(), f"max-abs error {err} > {TOL[batch.dtype]} (|out| up to {np.abs(want).max():.2f})"
     lerr = 0.0
     if lse is not None:
         gl = lse.double().cpu().numpy()

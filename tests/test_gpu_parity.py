@@ -174,6 +174,21 @@ def test_wavefront_items_on_forests(wave_kv, layout):
         assert list(st.tile_histogram)[2] > 0
 
 
+def test_short_unshared_batch_takes_the_wavefront_tile_by_itself():
+    # the planner's own choice of n = 32: 2048 unshared requests of up to 384 tokens, every request
+    # against the oracle
+    rng = np.random.default_rng(9)
+    lens = rng.integers(1, 385, 2048)
+    b = wl.tree_batch([2048], [lambda r, n: lens], num_q_heads=16, num_kv_heads=4, dtype="bf16", seed=61)
+    _log("case short unshared batch")
+    tensors = wl.make_tensors(b, device="cuda")
+    out, lse, plan = run_hip(b, tensors)
+    st = plan.stats()
+    assert st.num_wave_items == 2048 * 4 and list(st.tile_histogram)[2] == 2048
+    err, lerr = compare_all_requests_in_groups(b, out, lse, tensors, group=512)
+    _log(f"short unshared: err={err:.2e} lse_err={lerr:.2e}")
+
+
 def test_wavefront_items_many_per_wavefront():
     # far more items than the 8 x 4 wavefronts of four persistent workgroups: every wavefront walks a
     # list of items, requesting the next item's rows while it finishes the current one
@@ -186,7 +201,7 @@ def test_wavefront_items_many_per_wavefront():
     assert st.num_workers == 4 and st.num_wave_items > 20 * 32
 
 
-@pytest.mark.parametrize("node_tokens", [64, 224, 240, 512])
+@pytest.mark.parametrize("node_tokens", [16, 32, 48, 240])
 def test_tile_follows_the_kv_length_of_a_small_group(node_tokens):
     # 5 requests x 4 heads = 20 rows: below the crossover the node runs as two 16-row blocks,
     # from it on as one 64-row packed workgroup per KV head; same attention either way
@@ -198,7 +213,7 @@ def test_tile_follows_the_kv_length_of_a_small_group(node_tokens):
     shared = [e for e in range(ex["num_entries"]) if ex["item_kv_len"][ex["entry_item"][e]] == node_tokens
               and np.diff(ex["item_req_off"])[ex["entry_item"][e]] == 5]
     tiles = sorted(int(ex["entry_tile"][e]) for e in shared)
-    assert tiles == ([1, 1] if node_tokens < 240 else [3])
+    assert tiles == ([1, 1] if node_tokens < 48 else [3])
 
 
 @pytest.mark.parametrize("layout", ["NHD", "HND"])

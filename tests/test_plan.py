@@ -459,3 +459,39 @@ def test_background_planning_gives_the_same_plan():
     assert ei.value.status == pb.PAT_ERR_BAD_PAGE_ID
     del jobs
     pb.plan_for_batch(batches[1], background=True)      # never finished: discarded on collection
+
+
+def test_tile_solver_admits_every_tile_that_is_built():
+    # the constraints of sec. "Multi-tile Kernel" restated for a CU of this GPU (LDS, bytes in
+    # flight against latency x bandwidth, registers): every tile the library holds a kernel for
+    # (the VALU cross-check tile aside) is in the feasible set, and oversized ones are not
+    from paper_2511_22333_amd import calibrate
+    tiles, need = calibrate.tile_solver()
+    feasible = {(t["m"], t["n"]) for t in tiles if t["feasible"]}
+    assert 32 * 1024 < need < 128 * 1024
+    for tid, m, n in calibrate.built_tiles():
+        if (m, n) != (16, 4):
+            assert (m, n) in feasible, (tid, m, n)
+    assert (256, 256) not in feasible and (128, 256) not in feasible      # LDS and registers
+    assert (128, 16) not in feasible                                      # too little in flight
+
+
+def test_short_unshared_batches_run_as_wavefront_items():
+    # tile n follows the KV length: a launch of many rounds made of nothing but unshared requests
+    # of up to 384 tokens takes the n = 32 tile (one wavefront per request and KV head, no cuts);
+    # one long request, or a shared prefix, keeps the n = 128 tile
+    rng = np.random.default_rng(9)
+    lens = rng.integers(20, 385, 2048)
+    short = wl.tree_batch([2048], [lambda r, n: lens], num_q_heads=32, num_kv_heads=8, dtype="bf16", seed=9)
+    plan = pb.plan_for_batch(short)
+    check_schedule(short, plan)
+    st = plan.stats()
+    assert st.num_wave_items == 2048 * 8 and st.num_workers == 256 and st.num_slots == 0
+    assert list(st.tile_histogram)[:3] == [0, 0, 2048]
+    lens2 = lens.copy()
+    lens2[7] = 385
+    longer = wl.tree_batch([2048], [lambda r, n: lens2], num_q_heads=32, num_kv_heads=8, dtype="bf16", seed=9)
+    assert pb.plan_for_batch(longer).stats().num_wave_items == 0
+    assert pb.plan_for_batch(short, wave_kv_tokens=-1).stats().num_wave_items == 0
+    for name in ("C2", "C3", "C4", "C5"):
+        assert pb.plan_for_batch(wl.config(name)).stats().num_wave_items == 0
