@@ -128,7 +128,15 @@ typedef struct {
                                      /*   the caller's stream, 16-row tiles as 256-thread       */
                                      /*   workgroups (one KV head each, two per CU) on a stream */
                                      /*   of the plan's own that forks from and joins the       */
-                                     /*   caller's.  1 = on, -1 = off, 0 = the planner decides  */
+                                     /*   caller's.  1 = on; 0 or -1 = off (measured slower on  */
+                                     /*   MI355X, so never the planner's own choice)            */
+    int32_t fused_merge;             /* merge inside the forward launch (no second kernel): a   */
+                                     /*   per-(request, KV head) arrival counter tells the last */
+                                     /*   workgroup to arrive to merge that request's partials; */
+                                     /*   in launches of one round, workgroups that are done    */
+                                     /*   claim requests and wait (bounded) for their partials. */
+                                     /*   1 = on; 0 or -1 = off (measured slower than the merge */
+                                     /*   kernel on MI355X, so never the planner's own choice)  */
     int32_t packed_min_tokens;       /* 17..32 rows over fewer tokens than this run as two      */
                                      /*   16-row blocks, not as one 64-row packed workgroup;    */
                                      /*   0 = the built-in MI355X crossover (48)                */
@@ -152,6 +160,9 @@ typedef struct {
                                      /*   num_workgroups counts them next to the workgroup-     */
                                      /*   level units (one timeline record each)                */
     int32_t num_workers;             /* persistent workgroups of a launch with such items, or 0 */
+    int32_t fused_merge;             /* 0: forward then merge kernel; 1: the forward launch     */
+                                     /*   merges (last arriver); 2: the same with claimed waits */
+    int32_t pad0;
     int32_t tile_histogram[16];      /* entries per tile id                                     */
 } pat_plan_stats;
 
@@ -227,7 +238,9 @@ int pat_tile_info(int tile_id, int *m, int *n);
 /* forward (sec. "Multi-tile Kernel", sec. "Multi Kernel Forward"): for every work item and KV
  * head, S = scale * Q K^T over the item's tokens, online softmax, O = P V, fp32 accumulation.
  * Writes one fp32 partial (normalised O [d] and natural-log LSE) per (item, request, q head)
- * into the workspace, or the final out/lse directly for requests with a single item.
+ * into the workspace, or the final out/lse directly for requests with a single item.  Plans with
+ * the merge fused into this launch (pat_plan_stats.fused_merge != 0) also write the merged
+ * out/lse of every other request; pat_merge() after it is then redundant (and harmless).
  *   q          device [B][Hq][d], dtype, contiguous
  *   k_pool     device; element (page, token, kv head, c) at
  *   v_pool       page*kv_stride_page + token*kv_stride_token + head*kv_stride_head + c
@@ -277,6 +290,12 @@ int pat_decode_attention_static_ws(const pat_plan_t *plan, const void *q, const 
  * first tile landed for packed tiles).  NULL switches it off (the default).  Process-wide;
  * not thread-safe. */
 int pat_debug_set_trace(void *device_buf, size_t bytes);
+
+/* Debug aid for the fused merge's claimed waits: the number of polls (about 0.3 us each) a
+ * workgroup spends on a request whose partials are not complete before it leaves the request to
+ * the last arriver.  0 makes every wait give up at once (the fallback path, for tests); negative
+ * restores the default (4096).  Process-wide; not thread-safe. */
+int pat_debug_set_spin_limit(int polls);
 
 const char *pat_strerror(int status);
 const char *pat_version(void);

@@ -54,7 +54,7 @@ class pat_plan_opts(C.Structure):
                 ("num_cus", C.c_int32), ("tail_reserve_pages", C.c_int32),
                 ("model_ns", C.c_int32 * 4), ("wave_kv_tokens", C.c_int32),
                 ("wave_max_tokens", C.c_int32), ("dual_launch", C.c_int32),
-                ("packed_min_tokens", C.c_int32), ("reserved", C.c_int32 * 1)]
+                ("fused_merge", C.c_int32), ("packed_min_tokens", C.c_int32), ("reserved", C.c_int32 * 1)]
 
 
 class pat_plan_stats(C.Structure):
@@ -65,6 +65,7 @@ class pat_plan_stats(C.Structure):
                 ("unique_kv_tokens", C.c_int64), ("total_kv_tokens", C.c_int64),
                 ("plan_device_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
                 ("num_wave_items", C.c_int32), ("num_workers", C.c_int32),
+                ("fused_merge", C.c_int32), ("pad0", C.c_int32),
                 ("tile_histogram", C.c_int32 * 16)]
 
 
@@ -82,7 +83,7 @@ EXPORTED = ("pat_plan", "pat_plan_destroy", "pat_plan_get_stats", "pat_plan_expo
             "pat_plan_upload", "pat_num_tiles", "pat_tile_info", "pat_forward", "pat_merge",
             "pat_decode_attention", "pat_strerror", "pat_version", "pat_debug_set_trace",
             "pat_plan_advance", "pat_plan_start", "pat_plan_finish",
-            "pat_decode_attention_static_ws")
+            "pat_decode_attention_static_ws", "pat_debug_set_spin_limit")
 PAT_STATIC_WORKSPACE_BYTES = 32 << 20
 
 lib.pat_plan.argtypes = [C.POINTER(pat_batch_desc), C.POINTER(pat_plan_opts),
@@ -110,6 +111,7 @@ lib.pat_decode_attention_static_ws.argtypes = _fwd_args[:10] + [C.c_void_p]
 lib.pat_merge.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                           C.c_void_p]
 lib.pat_debug_set_trace.argtypes = [C.c_void_p, C.c_size_t]
+lib.pat_debug_set_spin_limit.argtypes = [C.c_int]
 lib.pat_strerror.argtypes = [C.c_int]
 lib.pat_strerror.restype = C.c_char_p
 lib.pat_version.restype = C.c_char_p
@@ -200,7 +202,7 @@ def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, page_size: int, n
              merge_factor: int = 0, split_policy: int = PAT_SPLIT_AUTO,
              split_target_tokens: int = 0, force_tile: int = -1, num_cus: int = 0,
              tail_reserve_pages: int = 0, model_ns=None, wave_kv_tokens: int = 0,
-             wave_max_tokens: int = 0, dual_launch: int = 0, packed_min_tokens: int = 0,
+             wave_max_tokens: int = 0, dual_launch: int = 0, packed_min_tokens: int = 0, fused_merge: int = 0,
              background: bool = False, node_parent: Optional[np.ndarray] = None,
              node_num_pages: Optional[np.ndarray] = None,
              req_leaf_node: Optional[np.ndarray] = None) -> Plan:
@@ -228,6 +230,7 @@ def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, page_size: int, n
     o.wave_kv_tokens, o.wave_max_tokens = int(wave_kv_tokens), int(wave_max_tokens)
     o.dual_launch = int(dual_launch)
     o.packed_min_tokens = int(packed_min_tokens)
+    o.fused_merge = int(fused_merge)
     if model_ns is not None:
         for i, x in enumerate(model_ns):
             o.model_ns[i] = int(x)
@@ -332,6 +335,10 @@ def pat_debug_set_trace(buf=None):
     else:
         _check(lib.pat_debug_set_trace(buf.data_ptr(), buf.numel() * buf.element_size()),
                "pat_debug_set_trace")
+
+
+def pat_debug_set_spin_limit(polls: int):
+    _check(lib.pat_debug_set_spin_limit(int(polls)), "pat_debug_set_spin_limit")
 
 
 def alloc_plan_buffers(plan: Plan, device="cuda"):

@@ -27,6 +27,8 @@ using namespace pat;
 // Debug aid: device buffer for per-workgroup timeline records of the next forward launches.
 static unsigned long long *g_trace_buf = nullptr;
 static size_t g_trace_records = 0;
+// Debug aid: polls a workgroup spends on a claimed merge task before it leaves it to the last arriver.
+static int g_spin_limit = 4096;
 
 extern "C" {
 
@@ -36,6 +38,12 @@ int pat_debug_set_trace(void *device_buf, size_t bytes)
         return PAT_ERR_INVALID_ARG;
     g_trace_buf = static_cast<unsigned long long *>(device_buf);
     g_trace_records = device_buf ? bytes / 64 : 0;
+    return PAT_OK;
+}
+
+int pat_debug_set_spin_limit(int polls)
+{
+    g_spin_limit = polls < 0 ? 4096 : polls;
     return PAT_OK;
 }
 
@@ -282,6 +290,13 @@ int pat_forward(const pat_plan_t *plan, const void *q, const void *k_pool, const
     a.queue_begin = plan->queue_begin;
     a.queue_workers = plan->queue_workers;
     a.queue_ctr = reinterpret_cast<int32_t *>(const_cast<unsigned char *>(dev) + plan->layout.queue_ctr);
+    a.fuse_mode = plan->fuse_mode;
+    a.n_merge = plan->stats.num_merge_requests;
+    a.spin_limit = g_spin_limit;
+    a.req_midx = reinterpret_cast<const int32_t *>(dev + plan->layout.req_midx);
+    a.merge_rec = reinterpret_cast<const int32_t *>(dev + plan->layout.merge_rec);
+    a.req_slot_ids = reinterpret_cast<const int32_t *>(dev + plan->layout.req_slot_ids);
+    a.merge_state = reinterpret_cast<int32_t *>(const_cast<unsigned char *>(dev) + plan->layout.merge_state);
     a.workers = nullptr;
     a.wave_items = reinterpret_cast<const DevWaveItem *>(dev + plan->layout.wave_items);
     a.unit_base = 0;
@@ -347,6 +362,7 @@ int pat_decode_attention(const pat_plan_t *plan, const void *q, const void *k_po
                          kv_stride_head, softmax_scale, out, lse, workspace, workspace_bytes,
                          stream);
     if (rc != PAT_OK) return rc;
+    if (plan->fuse_mode) return PAT_OK;                 // the forward launch has merged
     return pat_merge(plan, out, lse, workspace, workspace_bytes, stream);
 }
 

@@ -103,6 +103,12 @@ struct FwdArgs {
     int32_t queue_begin;          // units from here on are taken from a queue by persistent workgroups
     int32_t queue_workers;        // how many of those (the last workgroups of the grid); 0: no queue
     int32_t *queue_ctr;           // [0]: next queued unit, [1]: workers that have left; both 0 between launches
+    // merge fused into the launch (fuse_mode != 0)
+    int32_t fuse_mode, n_merge, spin_limit;
+    const int32_t *req_midx;      // parallel to req_ids: merge record of the request or -1
+    const int32_t *merge_rec;     // 128-byte merge records
+    const int32_t *req_slot_ids;
+    int32_t *merge_state;         // [n_merge][Hkv] task state words
     int32_t unit_base;            // unit of workgroup 0 (the 16-row kernel of a two-kernel launch)
     const DevWorker *workers;     // launches with wavefront items: one record per persistent workgroup
     const DevWaveItem *wave_items;
@@ -208,6 +214,31 @@ __device__ __forceinline__ void store16_stream(float *p, float x, float y, float
     __builtin_nontemporal_store(f32x4{x, y, z, w}, reinterpret_cast<f32x4 *>(p));
 }
 
+// Partials that are merged INSIDE the launch that writes them (by a workgroup on another XCD, whose
+// L2 is not coherent with this one's): stored and loaded at agent scope, i.e. written through and
+// read past the L2s, so that an arrival counter can order them without flushing a whole L2 per
+// workgroup (a device-wide fence does that, and costs more than the merge kernel it would save).
+__device__ __forceinline__ void store16_agent(float *p, float x, float y, float z, float w)
+{
+    const f32x4 v = {x, y, z, w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store1_agent(float *p, float x)
+{
+    __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <bool AGENT>
+__device__ __forceinline__ float load1(const float *p)
+{
+    return AGENT ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
+}
+template <bool AGENT>
+__device__ __forceinline__ float4 load4(const float *p)
+{
+    if (!AGENT) return *reinterpret_cast<const float4 *>(p);
+    return make_float4(load1<true>(p), load1<true>(p + 1), load1<true>(p + 2), load1<true>(p + 3));
+}
+
 // LDS the single forward kernel reserves.  The 16-row tiles run on 256-thread halves of the
 // workgroup with half of it each; the packed tiles use all of it.
 constexpr int kHalfSmemBytes = 36864;
@@ -221,9 +252,15 @@ __device__ __forceinline__ void store_row_chunk(const FwdArgs &a, int slot, int 
 {
     if (slot >= 0) {
         float *dst = a.part_o + ((int64_t)slot * a.Hq + head) * kHeadDim + c0;
-        store16_stream(dst, o[0], o[1], o[2], o[3]);
-        store16_stream(dst + 4, o[4], o[5], o[6], o[7]);
-        if (lse_lane) a.part_lse[(int64_t)slot * a.Hq + head] = lse;
+        if (a.fuse_mode) {                              // uniform: merged inside this launch
+            store16_agent(dst, o[0], o[1], o[2], o[3]);
+            store16_agent(dst + 4, o[4], o[5], o[6], o[7]);
+            if (lse_lane) store1_agent(a.part_lse + (int64_t)slot * a.Hq + head, lse);
+        } else {
+            store16_stream(dst, o[0], o[1], o[2], o[3]);
+            store16_stream(dst + 4, o[4], o[5], o[6], o[7]);
+            if (lse_lane) a.part_lse[(int64_t)slot * a.Hq + head] = lse;
+        }
     } else {
         uint16_t *dst = a.out + ((int64_t)req * a.Hq + head) * kHeadDim + c0;
         uint32_t pk[4];

@@ -15,6 +15,7 @@
 // register file).  Packed tiles run all eight wavefronts on one KV head (4 row groups x 2
 // token halves); the 16-row tiles run two KV heads side by side, one per 256-thread half.
 // The compiler allocates v0..v223 only: the packed tile keeps loads in flight in v224..v255.
+#include "pat_merge_core.cuh"
 #include "pat_tile_packed.cuh"
 #include "pat_tile_stream16.cuh"
 #include "pat_tile_valu16.cuh"
@@ -73,12 +74,119 @@ __device__ __forceinline__ void run_unit(const FwdArgs &a, int u, unsigned char 
     }
 }
 
+// ---- merge inside the forward launch (sec. "Output Merge" without a second kernel) ---------------
+// Every (request with several partials, KV head) is a task with a state word: arrivals so far and
+// two flags.  A workgroup that has stored its unit's partials makes them visible (fence), then
+// adds one arrival to the task of every (request, KV head) its unit holds rows of.
+//   Tasks nobody waits for ("abandoned"; all tasks of launches of many rounds): the workgroup whose
+//   arrival completes the task merges it there and then.  Nothing ever waits.
+//   Launches of one round: workgroups that are done with their unit also claim tasks in order
+//   and poll, a bounded number of times, until the task's arrivals are complete, then merge it --
+//   so the merges of a batch under one long shared prefix, whose partials all arrive at the very end,
+//   are spread over the whole chip instead of falling to the last packed workgroup of each head.  A
+//   claimer that runs out of polls marks the task abandoned and leaves: the arrival that completes
+//   it sees the mark and merges.  Both sides decide on one atomic word, so exactly one of them merges.
+// The merger puts the word back to its initial value; the last workgroup out resets the claim counters.
+template <typename T>
+__device__ __forceinline__ void fused_merge_task(const FwdArgs &a, int task)
+{
+    MergeArgs m;
+    m.merge_rec = a.merge_rec;
+    m.req_slot_ids = a.req_slot_ids;
+    m.part_o = a.part_o;
+    m.part_lse = a.part_lse;
+    m.out = a.out;
+    m.lse = a.lse;
+    m.n_merge = a.n_merge;
+    m.Hq = a.Hq;
+    m.long_lists = 1;
+    const int midx = task / a.Hkv, g = task % a.Hkv;
+    const int32_t *rec = a.merge_rec + (int64_t)midx * kMergeRecInts;
+    int tx = threadIdx.x;
+    asm volatile("" : "+v"(tx));
+    for (int hh = __builtin_amdgcn_readfirstlane(tx >> 6); hh < a.G; hh += 8)
+        merge_head_lists<T, true>(m, rec, g * a.G + hh, tx & 63);
+}
+
+template <typename T>
+__device__ __forceinline__ void fused_merge(const FwdArgs &a, int u)
+{
+    __shared__ int s_ready[160];
+    __shared__ int s_n, s_task, s_do;
+    const int init = a.fuse_mode == 1 ? kFuseAbandoned : 0;
+    int tx = threadIdx.x;
+    asm volatile("" : "+v"(tx));
+    // this thread's partials (agent-scope stores: written through) have been acknowledged
+    __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
+    if (tx == 0) s_n = 0;
+    __syncthreads();
+    {
+        const DevUnit *up = a.units + u;
+        const int G = a.G;
+        const int first = up->e.row_begin / G, last = (up->e.row_begin + up->e.n_rows - 1) / G;
+        const int nh = up->n_heads;
+        if (tx < (last - first + 1) * nh) {
+            const int midx = a.req_midx[up->e.req_off + first + tx / nh];
+            if (midx >= 0) {
+                const int task = midx * a.Hkv + up->kvh0 + tx % nh;
+                const int old = atomicAdd(a.merge_state + task, 1);
+                if ((old & kFuseCountMask) + 1 == a.merge_rec[midx * kMergeRecInts + 3] && (old & kFuseAbandoned))
+                    s_ready[atomicAdd(&s_n, 1)] = task;
+            }
+        }
+    }
+    __syncthreads();
+    const int n = s_n;
+    if (n > 0) {                                        // uniform
+        for (int i = 0; i < n; ++i) fused_merge_task<T>(a, s_ready[i]);
+        if (tx < n) a.merge_state[s_ready[tx]] = init;
+    }
+    if (a.fuse_mode != 2) return;
+    const int n_tasks = a.n_merge * a.Hkv;
+    for (;;) {
+        if (tx == 0) {
+            const int t = atomicAdd(a.queue_ctr, 1);
+            int take = 0;
+            if (t < n_tasks) {
+                const int expected = a.merge_rec[(t / a.Hkv) * kMergeRecInts + 3];
+                int cnt = atomicOr(a.merge_state + t, kFuseClaimed) & kFuseCountMask;
+                for (int it = 0; cnt != expected && it < a.spin_limit; ++it) {
+                    __builtin_amdgcn_s_sleep(32);
+                    cnt = __hip_atomic_load(a.merge_state + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) &
+                          kFuseCountMask;
+                }
+                if (cnt == expected)
+                    take = 1;
+                else
+                    take = (atomicOr(a.merge_state + t, kFuseAbandoned) & kFuseCountMask) == expected;
+            }
+            s_task = t;
+            s_do = take;
+        }
+        __syncthreads();
+        const int t = s_task, take = s_do;
+        __syncthreads();                                // s_task may be written again
+        if (t >= n_tasks) break;
+        if (take) {
+            fused_merge_task<T>(a, t);
+            if (tx == 0) a.merge_state[t] = init;
+        }
+    }
+    if (tx == 0) {
+        if (atomicAdd(a.queue_ctr + 1, 1) == (int)gridDim.x - 1) {
+            a.queue_ctr[0] = 0;
+            a.queue_ctr[1] = 0;
+        }
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(512, 2) __attribute__((amdgpu_num_vgpr(kVgprLimitAttr))) void forward_kernel(
     FwdArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[kFwdSmemBytes];
     run_unit<T, false>(a, blockIdx.x, smem);
+    if (a.fuse_mode) fused_merge<T>(a, blockIdx.x);
 }
 
 // The same with a queue: workgroups below queue_begin run their own unit, the others are

@@ -37,6 +37,8 @@ constexpr int32_t kPartialPermutedBit = 1 << 30;
 // ids themselves (bit 30 as above) -- so the merge kernel reaches the partials in two dependent
 // fetches instead of four.
 constexpr int kMergeRecInts = 32;
+// state word of a fused-merge task: arrivals so far, and who takes the merge
+constexpr int32_t kFuseCountMask = (1 << 20) - 1, kFuseClaimed = 1 << 29, kFuseAbandoned = 1 << 30;
 constexpr int kMergeInline = 28;
 
 // Zero page ids the planner appends to the device page-id list: the kernels prefetch ids a few
@@ -102,6 +104,7 @@ struct DevLayout {
     size_t merge_rec = 0, req_slot_off = 0, req_slot_ids = 0;
     size_t queue_ctr = 0;            // two counters of the 16-row unit queue (own 256 bytes)
     size_t workers = 0, wave_items = 0;
+    size_t req_midx = 0, merge_state = 0;     // fused merge: see pat_plan_s::fuse_mode
     size_t total = 0;
 };
 
@@ -135,6 +138,13 @@ struct pat_plan_s {
     bool dual = false;
     int32_t stream_begin = 0;
     void *side_stream = nullptr, *ev_fork = nullptr, *ev_join = nullptr;   // created by pat_plan_upload
+    // Merge fused into the forward launch.  0: off.  1: every (request, KV head) task has an
+    // arrival counter; the workgroup whose unit completes it merges the request.  2 (launches of
+    // one round): workgroups that are done also claim tasks in order and wait, bounded, for them.
+    // item_req_midx runs parallel to item_req_ids: index of the request's merge record or -1;
+    // a merge record's int 3 holds the arrivals that complete a task of that request.
+    int32_t fuse_mode = 0;
+    std::vector<int32_t> item_req_midx;
     // Launches with wavefront items run as `workers.size()` persistent workgroups instead.
     std::vector<pat::DevWorker> workers;
     std::vector<pat::DevWaveItem> wave_items;

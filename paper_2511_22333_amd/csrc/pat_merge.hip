@@ -18,7 +18,7 @@
 // partials of a request under a shared prefix come from packed tiles and are laid out that
 // way); partials in the true order are gathered with four 4-byte loads, and the result is
 // scattered back to the true order at the end.
-#include "pat_common.cuh"
+#include "pat_merge_core.cuh"
 
 namespace pat {
 
@@ -93,77 +93,10 @@ __global__ __launch_bounds__(256) void merge_kernel_pairs(MergeArgs a)
 template <typename T>
 __global__ __launch_bounds__(256) void merge_kernel_lists(MergeArgs a)
 {
-    const int lane = threadIdx.x & 63;
-    const int half = lane >> 5, j = lane & 31;
     const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (unit >= a.n_merge * a.Hq) return;               // whole wavefront leaves together
-    const int32_t *rec = a.merge_rec + (int64_t)(unit / a.Hq) * kMergeRecInts;
-    const int req = rec[0], n_total = rec[1], s0 = rec[2];
-    const int slot_inline = rec[4 + min(j, kMergeInline - 1)];  // fetched along with the header
-    const int head = unit % a.Hq;
-    // lane's elements: d' = 4 j + i, i = 0..3, i.e. d = 32 (j % 4) + 8 i + j / 4
-    const int d0 = 32 * (j & 3) + (j >> 2);
-    float mx = -INFINITY, total = 0.f;                  // total, acc: this half's share
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int c0 = 0; c0 < n_total; c0 += kMergeInline) {        // chunks of up to 28 partials
-        const int n = min(kMergeInline, n_total - c0);
-        int slot = 0;                                   // bit 30: partial in the d' order
-        float l = -INFINITY;
-        if (j < n) {                                    // the same list in both halves
-            slot = c0 == 0 ? slot_inline : a.req_slot_ids[s0 + c0 + j];
-            l = a.part_lse[(int64_t)(slot & ~kPartialPermutedBit) * a.Hq + head];
-        }
-        for (int i0 = 0; i0 < n; i0 += 16) {            // partial i0 + 2 k + half, k = 0..7
-            float4 o[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                o[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-                const int idx = i0 + 2 * k + half;
-                const int sraw = __shfl(slot, min(idx, 31), 64);        // (every lane takes part)
-                if (idx >= n) continue;
-                const float *row =
-                    a.part_o + ((int64_t)(sraw & ~kPartialPermutedBit) * a.Hq + head) * kHeadDim;
-                if (sraw & kPartialPermutedBit)
-                    o[k] = *reinterpret_cast<const float4 *>(row + 4 * j);
-                else
-                    o[k] = make_float4(row[d0], row[d0 + 8], row[d0 + 16], row[d0 + 24]);
-            }
-            // one maximum for both halves: over lanes i0 .. i0 + 15 of the list
-            float cm = (j >= i0 && j < i0 + 16) ? l : -INFINITY;
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) cm = fmaxf(cm, __shfl_xor(cm, off, 64));
-            cm = __shfl(cm, i0, 64);
-            const float m_new = fmaxf(mx, cm);
-            const float corr = __expf(mx - m_new);      // 0 on the first batch
-            total *= corr;
-            acc.x *= corr; acc.y *= corr; acc.z *= corr; acc.w *= corr;
-            mx = m_new;
-            const float w = __expf(l - mx);             // 0 for lanes without a partial
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int idx = i0 + 2 * k + half;
-                const float wk = __shfl(w, min(idx, 31), 64);
-                if (idx >= n) continue;
-                total += wk;
-                acc.x += wk * o[k].x; acc.y += wk * o[k].y;
-                acc.z += wk * o[k].z; acc.w += wk * o[k].w;
-            }
-        }
-    }
-    // the other half's share (same maximum in both)
-    total += __shfl_xor(total, 32, 64);
-    acc.x += __shfl_xor(acc.x, 32, 64);
-    acc.y += __shfl_xor(acc.y, 32, 64);
-    acc.z += __shfl_xor(acc.z, 32, 64);
-    acc.w += __shfl_xor(acc.w, 32, 64);
-    if (half != 0) return;
-    const float inv = 1.f / total;
-    uint16_t *dst = a.out + ((int64_t)req * a.Hq + head) * kHeadDim + d0;
-    dst[0] = Elem<T>::from_f32(acc.x * inv);
-    dst[8] = Elem<T>::from_f32(acc.y * inv);
-    dst[16] = Elem<T>::from_f32(acc.z * inv);
-    dst[24] = Elem<T>::from_f32(acc.w * inv);
-    if (a.lse && j == 0) a.lse[(int64_t)req * a.Hq + head] = mx + __logf(total);
+    merge_head_lists<T>(a, a.merge_rec + (int64_t)(unit / a.Hq) * kMergeRecInts, unit % a.Hq,
+                        threadIdx.x & 63);
 }
 
 hipError_t launch_merge(int dtype, const MergeArgs &a, hipStream_t s)

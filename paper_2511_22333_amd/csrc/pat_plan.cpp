@@ -384,6 +384,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     if (o.split_policy == PAT_SPLIT_TARGET && o.split_target_tokens < 1)
         return PAT_ERR_INVALID_ARG;
     if (o.merge_factor < 0 || o.num_cus < 0 || o.packed_min_tokens < 0) return PAT_ERR_INVALID_ARG;
+    if (o.fused_merge < -1 || o.fused_merge > 1 || o.dual_launch < -1 || o.dual_launch > 1) return PAT_ERR_INVALID_ARG;
     if (o.force_tile < -1 || o.force_tile >= NUM_TILES) return PAT_ERR_INVALID_ARG;
     if (o.force_tile >= 0 && !g_tile_available[o.force_tile]) return PAT_ERR_UNSUPPORTED;
     for (int32_t x : o.reserved)
@@ -930,6 +931,36 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
         }
     }
 
+    // ---- merge fused into the forward launch ----------------------------------------------------
+    // (plain single-kernel launches only: no unit queue, no wavefront items, no second stream)
+    std::vector<int32_t> merge_expected(pl.merge_req.size(), 0);
+    {
+        std::vector<int32_t> midx_of_req(B, -1);
+        for (size_t i = 0; i < pl.merge_req.size(); ++i) midx_of_req[pl.merge_req[i]] = (int32_t)i;
+        pl.item_req_midx.resize(pl.item_req_ids.size());
+        for (size_t i = 0; i < pl.item_req_ids.size(); ++i)
+            pl.item_req_midx[i] = pl.item_req_slot[i] >= 0 ? midx_of_req[pl.item_req_ids[i]] : -1;
+        // arrivals that complete a task (request, KV head): one per entry that holds rows of the
+        // request (the entry's workgroup for that head signals once per request it touches)
+        for (size_t e = 0; e < pl.entry_item.size(); ++e) {
+            const int32_t k = pl.entry_item[e], rb = pl.entry_row_begin[e], n = pl.entry_num_rows[e];
+            for (int32_t pos = rb / G; pos <= (rb + n - 1) / G; ++pos) {
+                const int32_t mi = pl.item_req_midx[pl.item_req_off[k] + pos];
+                if (mi >= 0) ++merge_expected[mi];
+            }
+        }
+        const bool plain = pl.queue_workers == 0 && pl.workers.empty() && !pl.dual;
+        pl.fuse_mode = 0;
+        // Measured on MI355X: slower than the merge kernel on every benchmark shape (C2 32.8 against
+        // 23.0 us per step, C3 126 against 110, C4 211 against 200).  A workgroup has to wait for
+        // its partial stores to be acknowledged from memory and then for an atomic's round trip
+        // before it may leave, with nothing in flight meanwhile, and the merge's own two dependent
+        // fetches come on top; the kernel boundary it replaces costs less than that chain.  So the
+        // planner uses it only where the caller asks for it.
+        if (o.fused_merge > 0 && plain && !pl.merge_req.empty() && o.force_tile != TILE_VALU16)
+            pl.fuse_mode = (int32_t)pl.units.size() <= cus ? 2 : 1;
+    }
+
     // ---- device image ----------------------------------------------------------------------
     DevLayout &L = pl.layout;
     size_t off = 0;
@@ -942,6 +973,8 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     L.req_slot_off = place(pl.req_slot_off.size() * 4);
     L.req_slot_ids = place(pl.req_slot_ids.size() * 4);
     L.queue_ctr = place(256);
+    L.req_midx = place(pl.item_req_midx.size() * 4);
+    L.merge_state = place(pl.merge_req.size() * (size_t)pl.Hkv * 4);
     L.workers = place(pl.workers.size() * sizeof(DevWorker));
     L.wave_items = place(pl.wave_items.size() * sizeof(DevWaveItem));
     L.total = std::max<size_t>(off, 256);
@@ -954,6 +987,12 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     put(L.req_slot, pl.item_req_slot.data(), pl.item_req_slot.size() * 4);
     put(L.page_ids, pl.pool_ids.data(), pl.pool_ids.size() * 4);
     put(L.req_slot_off, pl.req_slot_off.data(), pl.req_slot_off.size() * 4);
+    put(L.req_midx, pl.item_req_midx.data(), pl.item_req_midx.size() * 4);
+    {
+        // task state words start as "abandoned" where only the last arriver merges
+        std::vector<int32_t> st(pl.merge_req.size() * (size_t)pl.Hkv, pl.fuse_mode == 1 ? kFuseAbandoned : 0);
+        put(L.merge_state, st.data(), st.size() * 4);
+    }
     put(L.workers, pl.workers.data(), pl.workers.size() * sizeof(DevWorker));
     put(L.wave_items, pl.wave_items.data(), pl.wave_items.size() * sizeof(DevWaveItem));
     {
@@ -978,6 +1017,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
             rec[0] = r;
             rec[1] = n;
             rec[2] = s0;
+            rec[3] = merge_expected[i];
             for (int32_t k = 0; k < std::min<int32_t>(n, kMergeInline); ++k) rec[4 + k] = dev_ids[s0 + k];
         }
         put(L.merge_rec, recs.data(), recs.size() * 4);
@@ -997,6 +1037,7 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
     s.num_workgroups = (int32_t)(pl.units.size() + pl.wave_items.size());
     s.num_wave_items = (int32_t)pl.wave_items.size();
     s.num_workers = (int32_t)pl.workers.size();
+    s.fused_merge = pl.fuse_mode;
     s.num_slots = n_slots;
     s.num_merge_requests = (int32_t)pl.merge_req.size();
     s.unique_kv_tokens = unique_tokens;

@@ -504,13 +504,23 @@ __device__ __forceinline__ void tile_packed(const FwdArgs &a, const DevEntry &e,
     if (live && my_slot >= 0) {
         const int head = kvh * G + (e.row_begin + my_row) % G;
         float *dst = a.part_o + ((int64_t)my_slot * a.Hq + head) * kHeadDim + 4 * h;
+        if (a.fuse_mode) {                              // uniform: merged inside this launch
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+            for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                store16_stream(dst + 32 * b + 8 * j, acc[b][4 * j] * inv, acc[b][4 * j + 1] * inv,
-                               acc[b][4 * j + 2] * inv, acc[b][4 * j + 3] * inv);
-        if (h == 0) a.part_lse[(int64_t)my_slot * a.Hq + head] = lse;
+                for (int j = 0; j < 4; ++j)
+                    store16_agent(dst + 32 * b + 8 * j, acc[b][4 * j] * inv, acc[b][4 * j + 1] * inv,
+                                  acc[b][4 * j + 2] * inv, acc[b][4 * j + 3] * inv);
+            if (h == 0) store1_agent(a.part_lse + (int64_t)my_slot * a.Hq + head, lse);
+        } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    store16_stream(dst + 32 * b + 8 * j, acc[b][4 * j] * inv, acc[b][4 * j + 1] * inv,
+                                   acc[b][4 * j + 2] * inv, acc[b][4 * j + 3] * inv);
+            if (h == 0) a.part_lse[(int64_t)my_slot * a.Hq + head] = lse;
+        }
     }
     if (__builtin_amdgcn_ballot_w64(live && my_slot < 0) == 0) return;      // uniform
     float *os = reinterpret_cast<float *>(smem) + rg * 16 * kOsPitch;

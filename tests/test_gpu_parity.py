@@ -254,6 +254,42 @@ def test_two_kernel_launch_on_forests_and_in_a_graph(layout):
             compare(b, out, lse, want, want_lse)
 
 
+@pytest.mark.parametrize("spin_limit", [0, 3, -1])
+@pytest.mark.parametrize("fused", [1, -1])
+def test_merge_inside_the_forward_launch(fused, spin_limit):
+    # fused_merge: the forward launch merges (arrival counters; in launches of one round, claimed
+    # and bounded waits).  spin_limit 0 makes every claimed wait give up at once, so the arrival that
+    # completes a request merges it (the fallback); 3 mixes both; -1 is the default.  Against the
+    # oracle, twice per plan (the state words and counters must be back to their initial values).
+    pb.pat_debug_set_spin_limit(spin_limit)
+    try:
+        cases = [wl.random_forest_batch(s, dtype="bf16" if s % 2 else "fp16", max_requests=30,
+                                        max_node_tokens=300, num_q_heads=16, num_kv_heads=4,
+                                        duplicate_rows=(s % 3 == 0)) for s in (0, 1, 5)]
+        cases.append(wl.tree_batch([1, 24], [1024, lambda rng, n: rng.integers(1, 300, n)],
+                                   num_q_heads=32, num_kv_heads=8, dtype="bf16", seed=71))     # one round
+        cases.append(wl.tree_batch([2, 8, 400], [512, 256, lambda rng, n: rng.integers(1, 200, n)],
+                                   num_q_heads=16, num_kv_heads=8, dtype="bf16", seed=72))     # many rounds
+        for b in cases:
+            _log(f"case fused merge={fused} spin={spin_limit} B={b.num_requests}")
+            cpu = wl.make_tensors(b, poison=True)
+            want, want_lse = run_oracle(b, cpu)
+            q, kp, vp, st = to_gpu(cpu)
+            plan = pb.plan_for_batch(b, fused_merge=fused)
+            assert (plan.stats().fused_merge != 0) == (fused == 1)
+            dev, ws = pb.alloc_plan_buffers(plan)
+            pb.pat_plan_upload(plan, dev)
+            for _ in range(2):
+                out = torch.full_like(q, float("nan"))
+                lse = torch.full((b.num_requests, b.num_q_heads), float("nan"), dtype=torch.float32, device="cuda")
+                ws.fill_(0xFF)
+                pb.pat_decode_attention(plan, q, kp, vp, st, b.softmax_scale, out, lse, ws)
+                torch.cuda.synchronize()
+                compare(b, out, lse, want, want_lse)
+    finally:
+        pb.pat_debug_set_spin_limit(-1)
+
+
 def test_debug_trace_records_every_workgroup():
     b = wl.config("C1")
     q, kp, vp, st = to_gpu(wl.make_tensors(b))
