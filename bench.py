@@ -29,6 +29,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 REPLAYS = 5
+WARM_REPLAYS = 3
 
 
 def log(*a):
@@ -103,7 +104,8 @@ class Timer:
 
     def stats(self, g, n, how="wall"):
         fn = self.replay_us if how == "wall" else self.replay_event_us
-        fn(g, n)                                    # warm-up replay
+        for _ in range(WARM_REPLAYS):               # untimed: clocks and caches settle
+            fn(g, n)
         runs = sorted(fn(g, n) for _ in range(REPLAYS))
         return {"median": runs[len(runs) // 2], "mean": sum(runs) / len(runs),
                 "min": runs[0], "max": runs[-1]}

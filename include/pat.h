@@ -223,6 +223,22 @@ int pat_plan_finish(pat_plan_job_t *job, pat_plan_t **out_plan);
 int pat_plan_advance(pat_plan_t *plan, const int32_t *new_kv_lens, const int32_t *block_tables,
                      int32_t max_pages_per_req);
 
+/* Plan cache keyed by a fingerprint of the block table (sec. "Pack Scheduler": the schedule is
+ * reused while the block table stays the same and updated lazily when it grows).
+ * pat_plan_cache_get() hands out the plan for `batch` and says in *how (may be NULL) where it came
+ * from: 1 = the same batch (same kv_lens, same used block-table entries, same heads, dtype and
+ * options) was planned before: that plan, unchanged (its uploaded copy, if any, is still good);
+ * 2 = a cached batch some decode steps later (no request shorter, old pages in place): that plan
+ * brought up to date with pat_plan_advance() -- upload it again; 0 = planned anew (the least
+ * recently used plan is destroyed when `capacity` plans are held).  The cache owns the plans: they
+ * live until they are evicted or the cache is destroyed, and must not be passed to
+ * pat_plan_destroy().  Not thread-safe. */
+typedef struct pat_plan_cache_s pat_plan_cache_t;
+int pat_plan_cache_create(int32_t capacity, pat_plan_cache_t **out_cache);
+void pat_plan_cache_destroy(pat_plan_cache_t *cache);
+int pat_plan_cache_get(pat_plan_cache_t *cache, const pat_batch_desc *batch, const pat_plan_opts *opts,
+                       pat_plan_t **out_plan, int32_t *how);
+
 /* Copy the schedule into caller-owned device memory (>= stats.plan_device_bytes, 256-byte
  * aligned) with hipMemcpyAsync on `stream`; the buffer must outlive every forward/merge call
  * made with this plan.  The host staging copy is pageable, so the call returns after the

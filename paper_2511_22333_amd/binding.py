@@ -83,7 +83,8 @@ EXPORTED = ("pat_plan", "pat_plan_destroy", "pat_plan_get_stats", "pat_plan_expo
             "pat_plan_upload", "pat_num_tiles", "pat_tile_info", "pat_forward", "pat_merge",
             "pat_decode_attention", "pat_strerror", "pat_version", "pat_debug_set_trace",
             "pat_plan_advance", "pat_plan_start", "pat_plan_finish",
-            "pat_decode_attention_static_ws", "pat_debug_set_spin_limit")
+            "pat_decode_attention_static_ws", "pat_debug_set_spin_limit", "pat_plan_cache_create",
+            "pat_plan_cache_destroy", "pat_plan_cache_get")
 PAT_STATIC_WORKSPACE_BYTES = 32 << 20
 
 lib.pat_plan.argtypes = [C.POINTER(pat_batch_desc), C.POINTER(pat_plan_opts),
@@ -101,6 +102,11 @@ lib.pat_plan_start.restype = C.c_int
 lib.pat_plan_finish.argtypes = [C.c_void_p, C.POINTER(C.c_void_p)]
 lib.pat_plan_finish.restype = C.c_int
 lib.pat_plan_advance.restype = C.c_int
+lib.pat_plan_cache_create.argtypes = [C.c_int32, C.POINTER(C.c_void_p)]
+lib.pat_plan_cache_destroy.argtypes = [C.c_void_p]
+lib.pat_plan_cache_destroy.restype = None
+lib.pat_plan_cache_get.argtypes = [C.c_void_p, C.POINTER(pat_batch_desc), C.POINTER(pat_plan_opts),
+                                   C.POINTER(C.c_void_p), C.POINTER(C.c_int32)]
 lib.pat_num_tiles.restype = C.c_int
 lib.pat_tile_info.argtypes = [C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
 _fwd_args = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
@@ -160,7 +166,8 @@ class Plan:
     def destroy(self):
         # `lib` is already gone when the interpreter shuts down; the process ends anyway
         if getattr(self, "_h", None) is not None and self._h and lib is not None:
-            lib.pat_plan_destroy(self._h)
+            if not getattr(self, "_borrowed", False):
+                lib.pat_plan_destroy(self._h)
             self._h = None
 
     @property
@@ -197,15 +204,11 @@ class Plan:
         return out
 
 
-def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, page_size: int, num_pages: int,
-             num_q_heads: int, num_kv_heads: int, head_dim: int, dtype, mode: int = PAT_MODE_PAT,
-             merge_factor: int = 0, split_policy: int = PAT_SPLIT_AUTO,
-             split_target_tokens: int = 0, force_tile: int = -1, num_cus: int = 0,
-             tail_reserve_pages: int = 0, model_ns=None, wave_kv_tokens: int = 0,
-             wave_max_tokens: int = 0, dual_launch: int = 0, packed_min_tokens: int = 0, fused_merge: int = 0,
-             background: bool = False, node_parent: Optional[np.ndarray] = None,
-             node_num_pages: Optional[np.ndarray] = None,
-             req_leaf_node: Optional[np.ndarray] = None) -> Plan:
+def _desc_and_opts(block_tables, kv_lens, *, page_size, num_pages, num_q_heads, num_kv_heads, head_dim,
+                   dtype, mode=PAT_MODE_PAT, merge_factor=0, split_policy=PAT_SPLIT_AUTO,
+                   split_target_tokens=0, force_tile=-1, num_cus=0, tail_reserve_pages=0, model_ns=None,
+                   wave_kv_tokens=0, wave_max_tokens=0, dual_launch=0, packed_min_tokens=0, fused_merge=0,
+                   node_parent=None, node_num_pages=None, req_leaf_node=None):
     bt = np.ascontiguousarray(block_tables, dtype=np.int32)
     kl = np.ascontiguousarray(kv_lens, dtype=np.int32)
     d = pat_batch_desc()
@@ -234,6 +237,14 @@ def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, page_size: int, n
     if model_ns is not None:
         for i, x in enumerate(model_ns):
             o.model_ns[i] = int(x)
+    return d, o, keep
+
+
+def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, background: bool = False, **kw) -> Plan:
+    """pat_plan (or pat_plan_start with background=True); keywords: the fields of pat_batch_desc
+    (page_size, num_pages, num_q_heads, num_kv_heads, head_dim, dtype, optional tree) and of
+    pat_plan_opts."""
+    d, o, keep = _desc_and_opts(block_tables, kv_lens, **kw)
     if background:
         job = C.c_void_p()
         _check(lib.pat_plan_start(C.byref(d), C.byref(o), C.byref(job)), "pat_plan_start")
@@ -241,6 +252,36 @@ def pat_plan(block_tables: np.ndarray, kv_lens: np.ndarray, *, page_size: int, n
     h = C.c_void_p()
     _check(lib.pat_plan(C.byref(d), C.byref(o), C.byref(h)), "pat_plan")
     return Plan(h.value, keep)
+
+
+class PlanCache:
+    """Owner of one pat_plan_cache_t.  get() returns (Plan, how); the Plan objects do not own their
+    handles (the cache does) and are valid until evicted or the cache is closed."""
+
+    def __init__(self, capacity: int):
+        h = C.c_void_p()
+        _check(lib.pat_plan_cache_create(int(capacity), C.byref(h)), "pat_plan_cache_create")
+        self._h = h
+
+    def get(self, batch, **kw):
+        d, o, _ = _desc_and_opts(batch.block_tables, batch.kv_lens, page_size=batch.page_size,
+                                 num_pages=batch.num_pages, num_q_heads=batch.num_q_heads,
+                                 num_kv_heads=batch.num_kv_heads, head_dim=batch.head_dim,
+                                 dtype=batch.dtype, **kw)
+        h, how = C.c_void_p(), C.c_int32(-1)
+        _check(lib.pat_plan_cache_get(self._h, C.byref(d), C.byref(o), C.byref(h), C.byref(how)),
+               "pat_plan_cache_get")
+        p = Plan.__new__(Plan)
+        p._h, p._keep, p.device_buf, p._borrowed = C.c_void_p(h.value), None, None, True
+        return p, how.value
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h and lib is not None:
+            lib.pat_plan_cache_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
 
 
 class PlanJob:

@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libpat.so")
 PROBE_LIB = os.path.join(HERE, "libpat_probe.so")       # measurement kernels (bench, calibration)
 
-SOURCES = ["pat_plan.cpp", "pat_api.hip", "pat_forward.hip", "pat_merge.hip"]
+SOURCES = ["pat_plan.cpp", "pat_cache.cpp", "pat_api.hip", "pat_forward.hip", "pat_merge.hip"]
 
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -495,3 +495,42 @@ def test_short_unshared_batches_run_as_wavefront_items():
     assert pb.plan_for_batch(short, wave_kv_tokens=-1).stats().num_wave_items == 0
     for name in ("C2", "C3", "C4", "C5"):
         assert pb.plan_for_batch(wl.config(name)).stats().num_wave_items == 0
+
+
+# ---- plan cache keyed by the block table ---------------------------------------------------------
+def test_plan_cache_hits_advances_and_evicts():
+    cache = pb.PlanCache(2)
+    b = _roomy(wl.tree_batch([1, 3, 9], [96, 48, lambda rng, n: rng.integers(5, 120, n)],
+                             num_q_heads=16, num_kv_heads=4, dtype="bf16", seed=31), extra=64)
+    p0, how = cache.get(b)
+    assert how == 0
+    check_schedule(b, p0)
+    p1, how = cache.get(b)                                     # the same batch: the same plan
+    assert how == 1 and p1.handle.value == p0.handle.value
+    wide = dataclasses.replace(b, block_tables=np.pad(b.block_tables, ((0, 0), (0, 5)), constant_values=-1))
+    p1, how = cache.get(wide)                                  # unused entries are not part of the key
+    assert how == 1 and p1.handle.value == p0.handle.value
+    p2, how = cache.get(b, mode=pb.PAT_MODE_NO_SHARING)        # other options: another plan
+    assert how == 0 and p2.handle.value != p0.handle.value
+    grown = wl.decode_steps(b, 3)
+    p3, how = cache.get(grown)                                 # decode steps later: advanced in place
+    assert how == 2 and p3.handle.value == p0.handle.value
+    check_schedule(grown, p3)
+    p4, how = cache.get(grown)
+    assert how == 1
+    # a changed page id in the middle of a row is neither the same batch nor a successor
+    other = dataclasses.replace(grown, block_tables=grown.block_tables.copy())
+    other.block_tables[2, 1] = (int(other.block_tables[2, 1]) + 1) % other.num_pages
+    p5, how = cache.get(other)
+    assert how == 0
+    check_schedule(other, p5)
+    # capacity 2: the no-sharing plan was the least recently used and is gone; asking again plans anew
+    _, how = cache.get(b, mode=pb.PAT_MODE_NO_SHARING)
+    assert how in (0, 2)
+    # a request that got shorter is not a successor
+    shorter = dataclasses.replace(other, kv_lens=other.kv_lens - 1)
+    _, how = cache.get(shorter)
+    assert how == 0
+    cache.close()
+    with pytest.raises(pb.PatError):
+        pb.PlanCache(0)
