@@ -292,14 +292,14 @@ def run_config(name, args, ceiling_gbps, headline):
         del plan2, dev2, ws2
 
     # ---- fp64 oracle on the host cores ----
-    # headline: a bounded sample of ~10-30 s (requests in index order until ~6e9 multiply-adds),
+    # headline: a bounded sample of ~10-30 core-seconds (requests in index order until ~2e10 multiply-adds),
     # timed, as the CPU baseline; the other shapes: eight requests, for the error only
     cpu_baseline, max_err = None, None
     if not args.no_cpu_baseline:
         lens = batch.kv_lens.astype(np.int64)
         if headline:
             cost = np.cumsum(lens * batch.num_q_heads * batch.head_dim * 2)
-            n_req = int(max(1, min(batch.num_requests, np.searchsorted(cost, 6e9) + 1)))
+            n_req = int(max(1, min(batch.num_requests, np.searchsorted(cost, 2e10) + 1)))
             ids = list(range(n_req))
         else:
             rng = np.random.default_rng(5)
