@@ -242,7 +242,11 @@ int pat_plan_cache_get(pat_plan_cache_t *cache, const pat_batch_desc *batch, con
 /* Copy the schedule into caller-owned device memory (>= stats.plan_device_bytes, 256-byte
  * aligned) with hipMemcpyAsync on `stream`; the buffer must outlive every forward/merge call
  * made with this plan.  The host staging copy is pageable, so the call returns after the
- * copy has been handed to the runtime. */
+ * copy has been handed to the runtime.
+ * The image also holds the launch's counters (the unit queue's head, the fused merge's arrival
+ * counts); every launch leaves them at zero for the next one.  A launch that did NOT run to its
+ * end (an execution fault, a device reset, a process that was stopped inside it) can leave them
+ * anywhere: after any failed or abandoned launch, upload the plan again before using it. */
 int pat_plan_upload(pat_plan_t *plan, void *device_buf, size_t device_bytes, void *stream);
 
 /* Tile shapes of the forward kernel family (sec. "Multi-tile Kernel"): m = query rows a

@@ -63,7 +63,7 @@ def build(verbose: bool = False, jobs: int = 4) -> str:
     return LIB
 
 
-RING_FIRST_VGPR = 224      # pat_tile_packed.cuh: v224..v255 hold loads in flight
+RING_FIRST_VGPR = 224      # pat_tile_packed.hip.h: v224..v255 hold loads in flight
 
 
 def check_forward_isa(objdir: str, verbose: bool = False) -> None:

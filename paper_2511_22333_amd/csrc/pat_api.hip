@@ -10,7 +10,7 @@
 #include <thread>
 #include <vector>
 
-#include "pat_common.cuh"
+#include "pat_common.hip.h"
 
 namespace pat {
 int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl);

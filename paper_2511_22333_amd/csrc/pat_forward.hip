@@ -15,11 +15,11 @@
 // register file).  Packed tiles run all eight wavefronts on one KV head (4 row groups x 2
 // token halves); the 16-row tiles run two KV heads side by side, one per 256-thread half.
 // The compiler allocates v0..v223 only: the packed tile keeps loads in flight in v224..v255.
-#include "pat_merge_core.cuh"
-#include "pat_tile_packed.cuh"
-#include "pat_tile_stream16.cuh"
-#include "pat_tile_valu16.cuh"
-#include "pat_tile_wave16.cuh"
+#include "pat_merge_core.hip.h"
+#include "pat_tile_packed.hip.h"
+#include "pat_tile_stream16.hip.h"
+#include "pat_tile_valu16.hip.h"
+#include "pat_tile_wave16.hip.h"
 
 namespace pat {
 

@@ -17,8 +17,8 @@
 // The accumulation runs in the packed tiles' head-dim order d' = 16 (d % 8) + d / 8 (most
 // partials of a request under a shared prefix come from packed tiles and are laid out that
 // way); partials in the true order are gathered with four 4-byte loads, and the result is
-// scattered back to the true order at the end.
-#include "pat_merge_core.cuh"
+// brought back to the true order through lane shuffles, so that a row leaves as whole 8-byte pieces.
+#include "pat_merge_core.hip.h"
 
 namespace pat {
 
@@ -80,14 +80,10 @@ __global__ __launch_bounds__(256) void merge_kernel_pairs(MergeArgs a)
             }
         }
     }
-    if (!owner) return;
     const float inv = 1.f / total;
-    uint16_t *dst = a.out + ((int64_t)req * a.Hq + head) * kHeadDim + d0;
-    dst[0] = Elem<T>::from_f32(acc.x * inv);
-    dst[8] = Elem<T>::from_f32(acc.y * inv);
-    dst[16] = Elem<T>::from_f32(acc.z * inv);
-    dst[24] = Elem<T>::from_f32(acc.w * inv);
-    if (a.lse && j == 0) a.lse[(int64_t)req * a.Hq + head] = mx + __logf(total);
+    store_row_in_order<T>(a.out + ((int64_t)req * a.Hq + head) * kHeadDim,
+                          make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv), lane, owner);
+    if (owner && a.lse && j == 0) a.lse[(int64_t)req * a.Hq + head] = mx + __logf(total);
 }
 
 template <typename T>

@@ -2,9 +2,31 @@
 // halves take the even and the odd partials of the request's list and are added at the end.  Used
 // by the merge kernel's "lists" mapping and by the forward kernel where it merges a request itself.
 #pragma once
-#include "pat_common.cuh"
+#include "pat_common.hip.h"
 
 namespace pat {
+
+// A 32-lane half holds one output row in the accumulation order: lane j has d = 32 (j % 4) + 8 i +
+// j / 4 in component i.  Hands lane t of the half the elements 4 t .. 4 t + 3 (already rounded to
+// T) and stores them as one 8-byte piece, so the half writes its 256-byte row whole.  Every lane of
+// the wavefront must call; only halves with `active` store.
+template <typename T>
+__device__ __forceinline__ void store_row_in_order(uint16_t *row, float4 v, int lane, bool active)
+{
+    const int t = lane & 31, i = (t & 7) >> 1;
+    const uint32_t p0 = (uint32_t)Elem<T>::from_f32(v.x) | (uint32_t)Elem<T>::from_f32(v.y) << 16;
+    const uint32_t p1 = (uint32_t)Elem<T>::from_f32(v.z) | (uint32_t)Elem<T>::from_f32(v.w) << 16;
+    uint32_t e[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        // element d = 4 t + c lives in lane 4 (d % 8) + d / 32, component (d % 32) / 8 = i
+        const int src = (lane & 32) + 4 * (4 * (t & 1) + c) + (t >> 3);
+        const uint32_t q0 = __shfl(p0, src, 64), q1 = __shfl(p1, src, 64);
+        const uint32_t q = (i & 2) ? q1 : q0;
+        e[c] = (i & 1) ? q >> 16 : q & 0xffffu;
+    }
+    if (active) *reinterpret_cast<uint2 *>(row + 4 * t) = make_uint2(e[0] | e[1] << 16, e[2] | e[3] << 16);
+}
 
 // rec: the request's 128-byte merge record.  Every lane of the wavefront must call.  AGENT: the
 // partials were written earlier in the SAME launch (at agent scope) and are read past the L2.
@@ -70,14 +92,10 @@ __device__ __forceinline__ void merge_head_lists(const MergeArgs &a, const int32
     acc.y += __shfl_xor(acc.y, 32, 64);
     acc.z += __shfl_xor(acc.z, 32, 64);
     acc.w += __shfl_xor(acc.w, 32, 64);
-    if (half != 0) return;
-    const float inv = 1.f / total;
-    uint16_t *dst = a.out + ((int64_t)req * a.Hq + head) * kHeadDim + d0;
-    dst[0] = Elem<T>::from_f32(acc.x * inv);
-    dst[8] = Elem<T>::from_f32(acc.y * inv);
-    dst[16] = Elem<T>::from_f32(acc.z * inv);
-    dst[24] = Elem<T>::from_f32(acc.w * inv);
-    if (a.lse && j == 0) a.lse[(int64_t)req * a.Hq + head] = mx + __logf(total);
+    const float inv = 1.f / total;                      // both halves hold the whole sums now
+    store_row_in_order<T>(a.out + ((int64_t)req * a.Hq + head) * kHeadDim,
+                          make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv), lane, half == 0);
+    if (a.lse && lane == 0) a.lse[(int64_t)req * a.Hq + head] = mx + __logf(total);
 }
 
 }  // namespace pat

@@ -27,8 +27,8 @@
 #pragma once
 #include <type_traits>
 
-#include "pat_common.cuh"
-#include "pat_lds_barrier.cuh"
+#include "pat_common.hip.h"
+#include "pat_lds_barrier.hip.h"
 
 namespace pat {
 

@@ -21,7 +21,7 @@
 // In S^T a lane holds 4 tokens of ONE query row, so the running max needs two cross-lane
 // steps and P goes from the accumulator registers straight into the next MFMA's operand.
 #pragma once
-#include "pat_common.cuh"
+#include "pat_common.hip.h"
 
 namespace pat {
 

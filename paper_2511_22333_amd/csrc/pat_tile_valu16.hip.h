@@ -7,7 +7,7 @@
 // state; the four states are combined through LDS at the end (sec. "Output Merge" applied
 // inside the workgroup).
 #pragma once
-#include "pat_common.cuh"
+#include "pat_common.hip.h"
 
 namespace pat {
 

@@ -16,7 +16,7 @@
 // v_mfma_f32_16x16x32).  The epilogue needs no LDS: a lane holds 32 consecutive head-dim elements
 // of its row.
 #pragma once
-#include "pat_common.cuh"
+#include "pat_common.hip.h"
 
 namespace pat {
 
