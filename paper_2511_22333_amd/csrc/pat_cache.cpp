@@ -64,9 +64,14 @@ void flatten(const pat_batch_desc &b, Entry &e)
     e.fingerprint = h;
 }
 
+// Field by field: the descriptor has padding, whose bytes a caller's copy need not define.
 bool same_shape(const Entry &a, const Entry &b)
 {
-    return std::memcmp(&a.desc, &b.desc, sizeof a.desc) == 0 &&
+    const pat_batch_desc &x = a.desc, &y = b.desc;
+    static_assert(sizeof(pat_plan_opts) % 4 == 0 && alignof(pat_plan_opts) == 4, "opts: int32 fields only");
+    return x.num_requests == y.num_requests && x.page_size == y.page_size && x.num_pages == y.num_pages &&
+           x.num_q_heads == y.num_q_heads && x.num_kv_heads == y.num_kv_heads && x.head_dim == y.head_dim &&
+           x.dtype == y.dtype && x.num_nodes == y.num_nodes &&
            std::memcmp(&a.opts, &b.opts, sizeof a.opts) == 0 && a.tree == b.tree;
 }
 
@@ -161,7 +166,12 @@ int pat_plan_cache_get(pat_plan_cache_t *cache, const pat_batch_desc *batch, con
             pat_plan_destroy(cache->entries.back().plan);
             cache->entries.pop_back();
         }
-        cache->entries.push_front(std::move(key));
+        try {
+            cache->entries.push_front(std::move(key));
+        } catch (const std::bad_alloc &) {
+            pat_plan_destroy(plan);
+            throw;
+        }
         *out_plan = plan;
         if (how) *how = 0;
         return PAT_OK;
