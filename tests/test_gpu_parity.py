@@ -40,7 +40,10 @@ def test_single_request_ragged_lengths(kv):
     parity(b)
 
 
-@pytest.mark.parametrize("heads", [(4, 4), (8, 8), (16, 8), (32, 8), (64, 8), (8, 1), (32, 32)])
+@pytest.mark.parametrize("heads", [(4, 4), (8, 8), (16, 8), (32, 8), (64, 8), (8, 1), (32, 32),
+                                   # odd head counts and group sizes that are no power of two: a last
+                                   # workgroup with one KV head, a merge wavefront with one q head
+                                   (3, 3), (6, 3), (3, 1), (5, 5), (12, 4), (1, 1)])
 def test_head_configurations(heads):
     hq, hkv = heads
     _log(f"case heads {hq}/{hkv}")
