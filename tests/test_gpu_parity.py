@@ -43,7 +43,10 @@ def test_single_request_ragged_lengths(kv):
 @pytest.mark.parametrize("heads", [(4, 4), (8, 8), (16, 8), (32, 8), (64, 8), (8, 1), (32, 32),
                                    # odd head counts and group sizes that are no power of two: a last
                                    # workgroup with one KV head, a merge wavefront with one q head
-                                   (3, 3), (6, 3), (3, 1), (5, 5), (12, 4), (1, 1)])
+                                   (3, 3), (6, 3), (3, 1), (5, 5), (12, 4), (1, 1),
+                                   # groups wider than a 16-row block, up to more rows per request than
+                                   # one packed tile of 64 holds
+                                   (32, 1), (64, 2), (71, 1), (40, 5)])
 def test_head_configurations(heads):
     hq, hkv = heads
     _log(f"case heads {hq}/{hkv}")
