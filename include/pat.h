@@ -66,7 +66,8 @@ typedef enum {
 
 /* Long-KV split policy (sec. "Multi Kernel Forward", paragraph "Long KV Split").
  * MEAN   : the paper's rule -- packs longer than the mean pack length are cut into
- *          ceil(len/mean) page-aligned parts of (almost) equal page count.
+ *          ceil(len/mean) page-aligned parts of (almost) equal page count, and into more
+ *          while a part of several pages is still longer than the mean.
  * NONE   : no splitting.
  * TARGET : packs longer than split_target_tokens are cut into ceil(len/target) parts.
  * AUTO   : TARGET with a target derived from the batch and the device's CU count so that the

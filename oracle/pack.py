@@ -181,7 +181,8 @@ def model_cost(packs: Sequence[Pack], d: int = 1) -> int:
 
 
 def long_kv_split(packs: Sequence[Pack], kv_lens: Sequence[int], P: int) -> List[Pack]:
-    """Cut every pack longer than the mean pack length into equal page-aligned parts."""
+    """Cut every pack longer than the mean pack length into equal page-aligned parts, as many as it
+    takes to bring every part of more than one page under the mean."""
     if not packs:
         return []
     mean = Fraction(sum(p.kv_len for p in packs), len(packs))
@@ -193,6 +194,10 @@ def long_kv_split(packs: Sequence[Pack], kv_lens: Sequence[int], P: int) -> List
         q = Fraction(p.kv_len) / mean
         parts = -(-q.numerator // q.denominator)          # ceil(len / mean)
         parts = min(parts, p.num_pages)
+        # parts are whole pages: while the longest part (the first: full pages) is still over the
+        # mean and a part has more than one page, cut once more
+        while parts < p.num_pages and Fraction(-(-p.num_pages // parts) * P) > mean:
+            parts += 1
         base, extra = divmod(p.num_pages, parts)
         start = p.start
         for i in range(parts):

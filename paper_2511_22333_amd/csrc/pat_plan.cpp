@@ -483,8 +483,15 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
         };
         switch (o.split_policy) {
         case PAT_SPLIT_MEAN:
-            for (size_t i = 0; i < packs.size(); ++i)
-                cuts[i].parts = parts_for(packs[i], unique_tokens, (int64_t)packs.size());
+            // (sec. "Multi Kernel Forward", "Long KV Split": parts that keep the length under the
+            // mean.)  Parts are whole pages: while the longest part, the first, is still over the
+            // mean and has more than one page, cut once more.
+            for (size_t i = 0; i < packs.size(); ++i) {
+                const int64_t pages = packs[i].n_pages, n = (int64_t)packs.size();
+                int64_t parts = parts_for(packs[i], unique_tokens, n);
+                while (parts > 1 && parts < pages && (pages + parts - 1) / parts * P * n > unique_tokens) ++parts;
+                cuts[i].parts = parts;
+            }
             break;
         case PAT_SPLIT_NONE: break;
         case PAT_SPLIT_TARGET:

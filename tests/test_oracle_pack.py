@@ -5,6 +5,8 @@ import json
 import os
 import random
 
+from fractions import Fraction
+
 import numpy as np
 import pytest
 
@@ -392,8 +394,47 @@ def test_benchmark_shapes_pack_one_per_node(name, n_packs):
     items = op.long_kv_split(packs, b.kv_lens, b.page_size)
     mean = sum(p.kv_len for p in packs) / len(packs)
     for it in items:
-        assert it.kv_len <= mean + 2 * b.page_size
+        assert it.kv_len <= mean or it.num_pages == 1       # "under the mean value", page permitting
     assert sum(p.kv_len for p in items) == b.unique_kv_tokens()
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_split_takes_the_fewest_equal_parts_that_stay_under_the_mean(seed):
+    # sec. "Multi Kernel Forward", "Long KV Split": a pack over the mean is cut into equal parts that keep the
+    # length under the mean.  Stated without the ceil(len/mean) shortcut: try 2, 3, ... parts of page counts as
+    # equal as possible, longer first, and take the first count whose every part has at most `mean` tokens --
+    # or one page per part where not even that brings them under.
+    rng = np.random.default_rng(900 + seed)
+    P = int(rng.choice([1, 4, 16]))
+    lens = [int(x) for x in rng.integers(1, 40 * P, int(rng.integers(2, 12)))]
+    if seed % 3 == 0:
+        lens.append(int(rng.integers(100 * P, 400 * P)))          # one very long pack drags the mean up
+    packs = [op.Pack((i,), 0, -(-n // P), n) for i, n in enumerate(lens)]
+    mean = Fraction(sum(lens), len(lens))
+    got = op.long_kv_split(packs, lens, P)
+    k = 0
+    for i, n in enumerate(lens):
+        pages = -(-n // P)
+        want = None
+        if n <= mean:
+            want = [(0, pages, n)]
+        else:
+            for parts in range(2, pages + 1):
+                base, extra = divmod(pages, parts)
+                cuts, start = [], 0
+                for j in range(parts):
+                    c = base + (1 if j < extra else 0)
+                    cuts.append((start, c, min(n, (start + c) * P) - start * P))
+                    start += c
+                if all(t <= mean for _, _, t in cuts) or parts == pages:
+                    want = cuts
+                    break
+            if want is None:                                      # a single page cannot be cut
+                want = [(0, pages, n)]
+        for s0, c, t in want:
+            assert (got[k].queries, got[k].start, got[k].num_pages, got[k].kv_len) == ((i,), s0, c, t)
+            k += 1
+    assert k == len(got)
 
 
 def test_partial_last_page_is_never_shared():
