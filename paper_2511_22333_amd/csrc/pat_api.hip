@@ -159,7 +159,10 @@ int pat_plan_export(const pat_plan_t *plan, pat_plan_view *v)
 {
     if (!plan || !v) return PAT_ERR_INVALID_ARG;
     try {
-        pat::refresh_view(*const_cast<pat_plan_t *>(plan));     // after pat_plan_advance()
+        // after pat_plan_advance(); two threads may export one plan at the same time
+        pat_plan_t *mut = const_cast<pat_plan_t *>(plan);
+        std::lock_guard<std::mutex> lock(mut->view_mutex);
+        pat::refresh_view(*mut);
     } catch (const std::bad_alloc &) {
         return PAT_ERR_OUT_OF_MEMORY;
     }

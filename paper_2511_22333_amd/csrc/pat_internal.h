@@ -3,6 +3,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <mutex>
 #include <vector>
 
 #include "pat.h"
@@ -127,6 +128,7 @@ struct pat_plan_s {
     std::vector<int32_t> item_unit_off, item_units;   // CSR: the workgroups of each item
     std::vector<int32_t> kv_lens, req_tail_item;      // current length; own last item or -1
     bool view_dirty = false;                          // item_page_off/ids lag behind the pool
+    std::mutex view_mutex;                            // pat_plan_export() brings the view up to date under it
     std::vector<int32_t> merge_req;              // requests with more than one partial
     std::vector<pat::DevUnit> units;             // one per workgroup, launch order
     // Units [queue_begin, units.size()) are 16-row units taken from a queue by queue_workers
