@@ -7,6 +7,7 @@ kernel-equivalence run, KV-length decision; sec. "Tile Selection").
     python -m paper_2511_22333_amd.calibrate equivalence   # every tile on a no-prefix batch, KV 1024
     python -m paper_2511_22333_amd.calibrate sweep-kv      # KV-length thresholds of the selector
     python -m paper_2511_22333_amd.calibrate model         # run-time model of the split (default)
+    python -m paper_2511_22333_amd.calibrate grid          # (B, L) trees x head settings x modes
 
 The run-time model:
 
@@ -238,6 +239,56 @@ def sweep_kv(kv_lens=(16, 32, 48, 64, 96, 128, 192, 256, 384, 512, 1024), groups
     return shared, leaves
 
 
+# ---- (B, L) trees x head settings x ablation modes (sec. "Kernel Performance", "Ablation Study") ---
+# The paper's twenty (B, L) pairs are in a figure that its text does not carry; these trees are
+# stand-ins in its notation: B = nodes per level (the last level is the batch), L = tokens per level.
+GRID_TREES = (
+    ([1, 16], [1024, 256]),
+    ([1, 64], [4096, 128]),
+    ([1, 256], [2048, 64]),
+    ([1, 4, 16], [128, 256, 1024]),           # the example of sec. "Experiment Setup"
+    ([1, 4, 64], [2048, 512, 128]),
+    ([1, 8, 64], [64, 512, 512]),
+    ([4, 64], [1024, 256]),
+    ([1, 2, 8, 64], [512, 512, 512, 128]),
+    ([16, 256], [2048, 64]),
+    ([128], [1024]),                           # no shared prefix
+)
+GRID_HEADS = ((64, 8), (32, 8), (16, 8), (32, 32))     # the four head settings of the paper
+GRID_MODES = (("pat", {}), ("naive", {"mode": pb.PAT_MODE_NAIVE_PER_NODE}),
+              ("fixed64", {"force_tile": 3}), ("no-sharing", {"mode": pb.PAT_MODE_NO_SHARING}))
+
+
+def grid(trees=GRID_TREES, heads=GRID_HEADS, modes=GRID_MODES, launches=20, copies=None, each=None):
+    """us per step (forward + merge, the fastest of three runs of `launches` back-to-back steps over
+    `copies` rotated KV pools; None: as many as make 1 GiB, at most 12, so that no step finds its KV
+    in the 256 MB last-level cache) of every mode on every (tree, head setting), FP16 as in the paper.
+    Returns [(B, L, (Hq, Hkv), unique MB, {mode: us}, max |out - out of the first mode|)];
+    each(row) is called as the rows come."""
+    rows = []
+    for B, L in trees:
+        for hq, hkv in heads:
+            b = wl.tree_batch(list(B), list(L), num_q_heads=hq, num_kv_heads=hkv, dtype="fp16",
+                              seed=7400 + 31 * len(rows), name="grid")
+            n_copies = copies or max(1, min(12, (1 << 30) // b.unique_kv_bytes()))
+            t = [wl.make_tensors(b, seed=7400 + i, device="cuda") for i in range(n_copies)]
+            us, ref, dev = {}, None, 0.0
+            for name, kw in modes:
+                times, out, _, _ = _time_forward(b, t, launches=launches, **kw)
+                us[name] = min(times)
+                o = out.float()
+                if ref is None:
+                    ref = o.clone()
+                else:
+                    dev = max(dev, float((o - ref).abs().max()))
+            rows.append((list(B), list(L), (hq, hkv), b.unique_kv_bytes() / 1e6, us, dev))
+            if each:
+                each(rows[-1])
+            del t
+        torch.cuda.empty_cache()
+    return rows
+
+
 def run_model():
     rows = []
     for b in _one_round_batches():
@@ -296,6 +347,20 @@ def main(argv=None):
         print("unshared requests:            kv   n = 128 (4 wavefronts)   n = 32 (1 wavefront)")
         for kv, a, c in leaves:
             print(f"{kv:34d} {a:22.1f} {c:22.1f}   {'n=128' if a < c else 'n=32'}")
+    elif what == "grid":
+        names = [n for n, _ in GRID_MODES]
+        print("us per step (forward + merge), FP16, head dim 128; speed-up = no-sharing / pat")
+        print(f"{'B':>16s} {'L':>22s} {'heads':>6s} {'MB':>7s} " + " ".join(f"{n:>10s}" for n in names)
+              + "  speed-up  GB/s(pat)", flush=True)
+
+        def show(row):
+            B, L, (hq, hkv), mb, us, dev = row
+            print(f"{str(B):>16s} {str(L):>22s} {hq:3d}/{hkv:<2d} {mb:7.1f} "
+                  + " ".join(f"{us[n]:10.1f}" for n in names)
+                  + f"  {us['no-sharing'] / us['pat']:8.2f}  {mb / us['pat'] * 1e3:9.0f}", flush=True)
+
+        rows = grid(each=show)
+        print(f"largest difference between the modes' outputs: {max(r[5] for r in rows):.2e}")
     else:
         run_model()
 

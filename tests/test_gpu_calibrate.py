@@ -44,3 +44,14 @@ def test_kv_sweep_runs():
     shared, leaves = calibrate.sweep_kv(kv_lens=(64, 512), groups=32)
     assert len(shared) == 2 and len(leaves) == 2
     assert all(a > 0 and c > 0 for _, a, c in shared + leaves)
+
+
+def test_grid_of_trees_gives_one_result_in_every_mode():
+    print("case grid", flush=True)
+    rows = calibrate.grid(trees=(([1, 4, 16], [128, 256, 100]), ([24], [300])), heads=((32, 8), (4, 4)),
+                          launches=2, copies=1)
+    assert len(rows) == 4
+    for B, L, heads, mb, us, dev in rows:
+        print(f"  {B} {L} {heads}: {us}, modes differ by {dev:.1e}", flush=True)
+        assert set(us) == {n for n, _ in calibrate.GRID_MODES} and all(v > 0 for v in us.values())
+        assert dev < 4e-3                                       # one attention, four schedules (fp16 output)
