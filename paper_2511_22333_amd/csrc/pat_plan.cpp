@@ -546,7 +546,37 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
                 longest = std::max<int64_t>(longest, is_packed(p) ? packed_c0(p) + packed_c1(p) * p.kv_len
                                                                 : c0s + 2 * c1s * p.kv_len);
             const int64_t share = (unique_tokens * Hkv + slots - 1) / slots;     // token-heads per slot
-            if (share > 1024) {                          // many rounds
+            // A launch played through with the run-time model: workgroups longest first, a CU takes the
+            // next one when it is free (wavefront items as workgroups that hold eight of them side by side).
+            auto wg_ns = [&](const Pack &p, const Cut &c) {
+                const int64_t L = (p.kv_len + c.parts - 1) / c.parts;
+                if (c.wave) return c0w + c1w * L;
+                return is_packed(p) ? packed_c0(p) + packed_c1(p) * L : c0s + c.heads_per_wg * c1s * L;
+            };
+            auto wg_count = [&](const Pack &p, const Cut &c) {
+                const int64_t rows = (int64_t)p.reqs.size() * G;
+                if (c.wave) return (c.parts * ((rows + 15) / 16) * Hkv + 7) / 8;
+                const int64_t wgs = is_packed(p) ? Hkv : (c.heads_per_wg == 1 ? Hkv : pair_wgs);
+                return c.parts * (is_packed(p) ? (rows + max_m - 1) / max_m : (rows + 15) / 16) * wgs;
+            };
+            auto launch_ns = [&](const std::vector<Cut> &cs) {
+                std::vector<std::pair<int64_t, int64_t>> jobs;          // (run time, how many)
+                for (size_t i = 0; i < packs.size(); ++i)
+                    jobs.emplace_back(wg_ns(packs[i], cs[i]), wg_count(packs[i], cs[i]));
+                std::sort(jobs.begin(), jobs.end(), std::greater<>());
+                std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> busy;
+                for (int64_t k = 0; k < slots; ++k) busy.push(0);
+                int64_t end = 0;
+                for (const auto &j : jobs)
+                    for (int64_t k = 0; k < j.second; ++k) {
+                        const int64_t t = busy.top() + j.first;
+                        busy.pop();
+                        busy.push(t);
+                        end = std::max(end, t);
+                    }
+                return end;
+            };
+            auto many_rounds_cut = [&]() {
                 // Workgroups are launched longest first and a CU takes the next one when it is
                 // free.  Two candidate cuts are played through that way with the run-time model
                 // above; the coarse one is taken unless it ends more than 5 % later (every cut costs
@@ -555,35 +585,6 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
                 //           launch is estimated to take is cut, into parts that do not;
                 //   fine:   a pack is cut where it exceeds half a slot's share of all
                 //           token-heads, whatever its tile.
-                // (wavefront items are played as workgroups that hold eight of them side by side)
-                auto wg_ns = [&](const Pack &p, const Cut &c) {
-                    const int64_t L = (p.kv_len + c.parts - 1) / c.parts;
-                    if (c.wave) return c0w + c1w * L;
-                    return is_packed(p) ? packed_c0(p) + packed_c1(p) * L : c0s + c.heads_per_wg * c1s * L;
-                };
-                auto wg_count = [&](const Pack &p, const Cut &c) {
-                    const int64_t rows = (int64_t)p.reqs.size() * G;
-                    if (c.wave) return (c.parts * ((rows + 15) / 16) * Hkv + 7) / 8;
-                    const int64_t wgs = is_packed(p) ? Hkv : (c.heads_per_wg == 1 ? Hkv : pair_wgs);
-                    return c.parts * (is_packed(p) ? (rows + max_m - 1) / max_m : (rows + 15) / 16) * wgs;
-                };
-                auto launch_ns = [&](const std::vector<Cut> &cs) {
-                    std::vector<std::pair<int64_t, int64_t>> jobs;          // (run time, how many)
-                    for (size_t i = 0; i < packs.size(); ++i)
-                        jobs.emplace_back(wg_ns(packs[i], cs[i]), wg_count(packs[i], cs[i]));
-                    std::sort(jobs.begin(), jobs.end(), std::greater<>());
-                    std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> busy;
-                    for (int64_t k = 0; k < slots; ++k) busy.push(0);
-                    int64_t end = 0;
-                    for (const auto &j : jobs)
-                        for (int64_t k = 0; k < j.second; ++k) {
-                            const int64_t t = busy.top() + j.first;
-                            busy.pop();
-                            busy.push(t);
-                            end = std::max(end, t);
-                        }
-                    return end;
-                };
                 std::vector<Cut> fine(packs.size(), Cut{1, 2}), coarse(packs.size(), Cut{1, 2});
                 int64_t total_ns = 0;
                 for (size_t i = 0; i < packs.size(); ++i) {
@@ -603,6 +604,9 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
                     coarse[i].parts = parts_for(p, std::max<int64_t>(whole - c0, 64 * c1), c1);
                 }
                 cuts = launch_ns(coarse) * 100 <= launch_ns(fine) * 105 ? coarse : fine;
+            };
+            if (share > 1024) {                          // many rounds
+                many_rounds_cut();
                 break;
             }
             const int64_t floor_bound = std::max(c0p, c0s) + 2000;
@@ -615,9 +619,25 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
             } else {
                 int64_t lo = floor_bound, hi = std::max(longest, floor_bound + 1);   // W(hi) minimal
                 if (workgroups(hi, single_heads) > slots) {
-                    for (size_t i = 0; i < packs.size(); ++i)
-                        cuts[i] = Cut{parts_for(packs[i], std::max<int64_t>(256, share), 1), 2};
-                    break;                                          // cannot fit one round anyway
+                    // Cannot fit one round anyway: a few rounds.  Bounds on a workgroup's run time
+                    // from the floor up to the longest uncut workgroup, a third apart, are each
+                    // played through the launch (longest first, a CU takes the next when free); the
+                    // coarsest cut within 3 % of the earliest end is taken (every part more is one
+                    // more partial per row to write and merge, which the model does not price).
+                    std::vector<Cut> trial(packs.size(), Cut{1, 2}), best;
+                    std::vector<std::pair<int64_t, std::vector<Cut>>> played;
+                    int64_t earliest = INT64_MAX;
+                    for (int64_t t = floor_bound;; t = t * 4 / 3) {
+                        const int64_t tb = std::min(t, hi);
+                        for (size_t i = 0; i < packs.size(); ++i) trial[i] = cut_for(packs[i], tb, false);
+                        const int64_t end = launch_ns(trial);
+                        earliest = std::min(earliest, end);
+                        played.emplace_back(end, trial);
+                        if (tb == hi) break;
+                    }
+                    for (auto it = played.rbegin(); it != played.rend(); ++it)      // coarsest first
+                        if (it->first * 100 <= earliest * 103) { cuts = it->second; break; }
+                    break;
                 }
                 while (lo + 1 < hi) {                               // W(lo) > slots >= W(hi)
                     const int64_t mid = (lo + hi) / 2;
