@@ -121,8 +121,9 @@ typedef struct {
     int32_t wave_kv_tokens;          /* 16-row packs of up to wave_max_tokens tokens are cut    */
                                      /*   into parts of at most this many tokens, each (part,   */
                                      /*   KV head) walked by ONE wavefront (tile n = 32).       */
-                                     /*   0 or negative = not used (the default: measured       */
-                                     /*   slower than n = 128 on MI355X)                        */
+                                     /*   0 = the planner's own rule (launches of nothing but   */
+                                     /*   unshared requests of up to 384 tokens; 16-row packs   */
+                                     /*   of up to 96 tokens beside anything); negative = never */
     int32_t wave_max_tokens;         /* 0 = 4 * wave_kv_tokens                                  */
     int32_t dual_launch;             /* forward as TWO kernels side by side (sec. "Multi-Stream */
                                      /*   Forward"): packed tiles as 512-thread workgroups on   */

@@ -459,15 +459,30 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
         // 384 tokens (by 36 % at 64 tokens, 21 % at 128, 7 % at 256); next to packed tiles or long
         // streams it does not (C3, C4: equal to 20 % slower -- eight independent streams per CU
         // crowd the packed tiles' loads out, and the static lists start behind the units).  So the
-        // planner picks it only for launches of many rounds in which EVERY pack is such a request.
-        bool all_short = many_rounds && o.split_policy == PAT_SPLIT_AUTO && o.wave_kv_tokens == 0;
-        for (size_t i = 0; i < packs.size() && all_short; ++i)
-            all_short = (int64_t)packs[i].reqs.size() * G <= 16 && packs[i].kv_len <= 384;
+        // planner picks it for launches of many rounds in which EVERY pack is such a request.
+        // Very short 16-row packs are another matter: a workgroup's start and end cost more than
+        // their stream, and as wavefront items they win even beside packed tiles (256 leaves of 64
+        // tokens under a 2048-token prefix: 46.8 -> 35.8 us with 32/8 heads, 103.7 -> 67.4 with 32/32;
+        // equal at 128 tokens).  Taken where every 16-row pack has at most 96 tokens and they would
+        // fill more than one round of workgroups by themselves.
+        const bool auto_wave = o.split_policy == PAT_SPLIT_AUTO && o.wave_kv_tokens == 0;
+        bool all_short = many_rounds && auto_wave, leaves_short = auto_wave;
+        int64_t short_wgs = 0;
+        for (size_t i = 0; i < packs.size(); ++i) {
+            const int64_t rows = (int64_t)packs[i].reqs.size() * G;
+            all_short = all_short && rows <= 16 && packs[i].kv_len <= 384;
+            if (rows > 32 || (rows > 16 && packs[i].kv_len >= packed_min)) continue;      // a packed tile
+            leaves_short = leaves_short && packs[i].kv_len <= 96;
+            short_wgs += (rows + 15) / 16 * ((b.num_kv_heads + 1) / 2);
+        }
+        leaves_short = leaves_short && short_wgs > (o.num_cus > 0 ? o.num_cus : 256);
         if (o.wave_kv_tokens > 0) {
             wave_kv = o.wave_kv_tokens;
             wave_max = o.wave_max_tokens > 0 ? o.wave_max_tokens : 4 * wave_kv;
         } else if (all_short) {
             wave_kv = wave_max = 384;
+        } else if (leaves_short) {
+            wave_kv = wave_max = 96;
         }
     }
     {
@@ -623,14 +638,20 @@ int build_plan(const pat_batch_desc &b, const pat_plan_opts &o, pat_plan_s &pl)
                     // from the floor up to the longest uncut workgroup, a third apart, are each
                     // played through the launch (longest first, a CU takes the next when free); the
                     // coarsest cut within 3 % of the earliest end is taken (every part more is one
-                    // more partial per row to write and merge, which the model does not price).
+                    // more partial per row to write and merge; priced as its bytes, 2 x 516 per q
+                    // head, at 4 bytes/ns, on top of the launch).
                     std::vector<Cut> trial(packs.size(), Cut{1, 2}), best;
                     std::vector<std::pair<int64_t, std::vector<Cut>>> played;
                     int64_t earliest = INT64_MAX;
                     for (int64_t t = floor_bound;; t = t * 4 / 3) {
                         const int64_t tb = std::min(t, hi);
-                        for (size_t i = 0; i < packs.size(); ++i) trial[i] = cut_for(packs[i], tb, false);
-                        const int64_t end = launch_ns(trial);
+                        for (size_t i = 0; i < packs.size(); ++i)
+                            trial[i] = is_wave(packs[i]) ? Cut{parts_for(packs[i], wave_kv, 1), 1, true}
+                                                         : cut_for(packs[i], tb, false);
+                        int64_t partial_rows = 0;
+                        for (size_t i = 0; i < packs.size(); ++i)
+                            partial_rows += trial[i].parts * (int64_t)packs[i].reqs.size();
+                        const int64_t end = launch_ns(trial) + partial_rows * b.num_q_heads * (2 * 516) / 4000;
                         earliest = std::min(earliest, end);
                         played.emplace_back(end, trial);
                         if (tb == hi) break;

@@ -497,6 +497,22 @@ def test_short_unshared_batches_run_as_wavefront_items():
         assert pb.plan_for_batch(wl.config(name)).stats().num_wave_items == 0
 
 
+def test_very_short_leaves_run_as_wavefront_items_beside_packed_tiles():
+    # 16-row packs of at most 96 tokens that would fill more than one round of workgroups by themselves
+    # run as wavefront items whatever else the launch holds; the shared prefix keeps its packed tile
+    b = wl.tree_batch([1, 256], [2048, 64], num_q_heads=32, num_kv_heads=8, dtype="fp16", seed=3)
+    plan = pb.plan_for_batch(b)
+    check_schedule(b, plan)
+    st = plan.stats()
+    hist = list(st.tile_histogram)
+    assert st.num_wave_items == 256 * 8 and hist[2] == 256 and hist[1] == 0 and hist[4] > 0
+    # leaves of 128 tokens, or few enough leaves for one round: 16-row workgroups as before
+    for B, L in (([1, 256], [2048, 128]), ([1, 48], [2048, 64])):
+        other = wl.tree_batch(B, L, num_q_heads=32, num_kv_heads=8, dtype="fp16", seed=3)
+        assert pb.plan_for_batch(other).stats().num_wave_items == 0
+    assert pb.plan_for_batch(b, wave_kv_tokens=-1).stats().num_wave_items == 0
+
+
 # ---- plan cache keyed by the block table ---------------------------------------------------------
 def test_plan_cache_hits_advances_and_evicts():
     cache = pb.PlanCache(2)
