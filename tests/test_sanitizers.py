@@ -31,7 +31,11 @@ def drivers(tmp_path_factory):
     subprocess.check_call(["gcc", "-std=c99", *SAN, "-fopenmp",
                            os.path.join(ROOT, "tests", "sanitize", "oracle_driver.c"),
                            os.path.join(ROOT, "oracle", "pat_oracle.c"), "-o", orc, "-lm"])
-    return plan, orc, out
+    cache = str(out / "cache_driver")
+    subprocess.check_call(["g++", "-std=c++17", *SAN, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+                           os.path.join(ROOT, "tests", "sanitize", "cache_driver.cpp"),
+                           os.path.join(CSRC, "pat_cache.cpp"), os.path.join(CSRC, "pat_plan.cpp"), "-o", cache])
+    return plan, orc, out, cache
 
 
 def _run(exe, path):
@@ -58,7 +62,7 @@ def _plan_case(path, batch, *, mode=0, split=0, target=0, force_tile=-1, num_cus
 
 
 def test_planner_under_sanitizers_random_forests(drivers):
-    exe, _, out = drivers
+    exe, _, out, _ = drivers
     for seed in range(30):
         b = wl.random_forest_batch(seed, max_requests=24, max_node_tokens=200,
                                    duplicate_rows=(seed % 3 == 0))
@@ -70,14 +74,33 @@ def test_planner_under_sanitizers_random_forests(drivers):
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5", "T3", "PK"])
 def test_planner_under_sanitizers_benchmark_shapes(drivers, name):
-    exe, _, out = drivers
+    exe, _, out, _ = drivers
     b = wl.config(name)
     for k, kw in enumerate([dict(), dict(mode=2), dict(split=1), dict(wave_kv=256), dict(dual=1)]):
         _run(exe, _plan_case(str(out / f"{name}_{k}.bin"), b, **kw))
 
 
+def test_planner_under_sanitizers_batches_of_a_few_rounds(drivers):
+    # the cut searched with the simulated launch, with and without wavefront items for very short leaves
+    exe, _, out, _ = drivers
+    for k, (B, L, hq, hkv) in enumerate([([1, 256], [2048, 64], 64, 8), ([1, 256], [2048, 64], 32, 32),
+                                         ([1, 64], [4096, 128], 32, 8), ([1, 4, 64], [2048, 512, 128], 16, 8),
+                                         ([16, 256], [2048, 64], 32, 8), ([1, 2, 8, 64], [512, 512, 512, 128], 64, 8)]):
+        b = wl.tree_batch(B, L, num_q_heads=hq, num_kv_heads=hkv, dtype="fp16", seed=50 + k)
+        for j, kw in enumerate([dict(), dict(wave_kv=-1), dict(num_cus=64)]):
+            assert "ok" in _run(exe, _plan_case(str(out / f"few{k}_{j}.bin"), b, **kw))
+
+
+def test_plan_cache_under_sanitizers(drivers):
+    *_, cache = drivers
+    r = subprocess.run([cache], env=ENV, stdout=subprocess.PIPE, stderr=subprocess.PIPE, timeout=300)
+    err = r.stderr.decode(errors="replace")
+    assert r.returncode == 0 and "Sanitizer" not in err and "runtime error" not in err, err[-3000:]
+    assert r.stdout.decode().strip() == "ok"
+
+
 def test_lazy_update_under_sanitizers(drivers):
-    exe, _, out = drivers
+    exe, _, out, _ = drivers
     for seed in range(8):
         b = wl.random_forest_batch(300 + seed, max_requests=12, max_node_tokens=150)
         b = dataclasses.replace(b, num_pages=b.num_pages + 4096)
@@ -101,7 +124,7 @@ def test_lazy_update_under_sanitizers(drivers):
 
 
 def test_planner_refuses_bad_input_under_sanitizers(drivers):
-    exe, _, out = drivers
+    exe, _, out, _ = drivers
     b = wl.config("C1")
     bad = dataclasses.replace(b, block_tables=b.block_tables.copy())
     bad.block_tables[2, 1] = b.num_pages + 5
@@ -116,7 +139,7 @@ def test_planner_refuses_bad_input_under_sanitizers(drivers):
 
 
 def test_oracle_under_sanitizers(drivers):
-    _, exe, out = drivers
+    _, exe, out, _ = drivers
     for seed, layout in ((1, "NHD"), (2, "HND"), (3, "NHD")):
         b = wl.random_forest_batch(seed, max_requests=6, max_node_tokens=60, num_q_heads=4, num_kv_heads=2,
                                    dtype="bf16" if seed % 2 else "fp16")
