@@ -263,12 +263,15 @@ def run_config(name, args, ceiling_gbps, headline):
     achieved = unique_bytes / (fwd_us["mean"] * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": stored_traffic(name, args.mode, st, unique_bytes),
+                "traffic": None, "traffic_detail": stored_traffic(name, args.mode, st, unique_bytes),
                 "kernel": "forward", "kernel_us_mean": round(fwd_us["mean"], 2),
                 "kernel_us_median": round(fwd_us["median"], 2),
                 "merge_us_median": round(mrg_us["median"], 2),
                 "frac_of_read_ceiling": round(achieved / ceiling_gbps, 4) if ceiling_gbps else None,
                 "algorithmic_bytes": unique_bytes, "algorithmic_bytes_with_qo_partials": algo_total}
+
+    if roofline["traffic_detail"]:       # HBM bytes per forward launch: fetched + written (counters, see source)
+        roofline["traffic"] = roofline["traffic_detail"].get("total_bytes")
 
     # ---- one-query-per-workgroup plan through the same kernels, timed the same way ----
     baseline_mode = None
@@ -422,6 +425,7 @@ def main():
         r.pop("cpu_baseline")
         rf = r.pop("roofline")
         r["traffic"] = rf["traffic"]
+        r["traffic_detail"] = rf["traffic_detail"]
         per_config.append(r)
     result = {
         "metric": "decode_attention_unique_kv_bandwidth", "value": head["step_gbps"], "unit": "GB/s",
