@@ -195,6 +195,32 @@ def test_short_unshared_batch_takes_the_wavefront_tile_by_itself():
     _log(f"short unshared: err={err:.2e} lse_err={lerr:.2e}")
 
 
+@pytest.mark.parametrize("case", [
+    # (B, L, heads, dtype): hundreds of very short leaves under packed prefixes -- the leaves run as
+    # wavefront items by the planner's own rule, the prefix as packed tiles cut by the few-round search
+    ([1, 320], [1008, (1, 96)], (32, 8), "bf16"),
+    ([2, 300], [(300, 1500), (1, 64)], (64, 8), "fp16"),           # ragged prefixes: leaves of up to 79
+    ([1, 4, 288], [704, 160, (1, 96)], (16, 8), "bf16"),
+    ([1, 260], [2048, (40, 96)], (8, 8), "fp16"),
+    # the same shapes with leaves too long for that rule: 16-row workgroups, cut searched the same way
+    ([1, 320], [1008, (1, 200)], (32, 8), "bf16"),
+    ([1, 96], [4096, (100, 160)], (64, 8), "fp16"),
+])
+def test_batches_of_a_few_rounds_with_short_leaves(case):
+    B, L, (hq, hkv), dtype = case
+    spec = [(lambda rng, n, lo=x[0], hi=x[1]: rng.integers(lo, hi + 1, n)) if isinstance(x, tuple) else x for x in L]
+    b = wl.tree_batch(B, spec, num_q_heads=hq, num_kv_heads=hkv, dtype=dtype, seed=hq + len(B))
+    _log(f"case few rounds B={B} L={L} heads={hq}/{hkv} {dtype}")
+    tensors = wl.make_tensors(b, device="cuda", poison=True)
+    out, lse, plan = run_hip(b, tensors)
+    st = plan.stats()
+    short = all(not isinstance(x, tuple) or x[1] <= 96 for x in L[-1:])
+    assert (st.num_wave_items > 0) == short, (st.num_wave_items, short)
+    err, lerr = compare_all_requests_in_groups(b, out, lse, tensors, group=128)
+    _log(f"  items={st.num_items} workgroups={st.num_workgroups} wave_items={st.num_wave_items} "
+         f"tiles={list(st.tile_histogram)[:5]} err={err:.2e} lse_err={lerr:.2e}")
+
+
 def test_wavefront_items_many_per_wavefront():
     # far more items than the 8 x 4 wavefronts of four persistent workgroups: every wavefront walks a
     # list of items, requesting the next item's rows while it finishes the current one
