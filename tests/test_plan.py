@@ -123,6 +123,29 @@ def test_planner_equals_plain_statement_on_random_forests(seed):
     assert _canon(_items(ex)) == _canon((p.queries, p.start, p.num_pages, p.kv_len) for p in want)
 
 
+@pytest.mark.parametrize("seed", range(100, 130))
+def test_planner_equals_plain_statement_on_larger_forests(seed):
+    # deeper and wider forests, longer nodes, other head settings: packs (split NONE),
+    # the paper's mean split and the one-pack-per-node mode all equal the plain statement
+    hq, hkv = [(8, 2), (32, 8), (64, 8), (16, 8), (32, 32)][seed % 5]
+    b = wl.random_forest_batch(seed, duplicate_rows=(seed % 4 == 1), max_requests=48, max_depth=6,
+                               max_node_tokens=[64, 400, 1200][seed % 3], num_q_heads=hq, num_kv_heads=hkv)
+    want_packs = op.plan_packs(b.block_tables, b.kv_lens, b.page_size)
+    plan = pb.plan_for_batch(b, split_policy=pb.PAT_SPLIT_NONE)
+    ex = check_schedule(b, plan)
+    assert _canon(_items(ex)) == _canon((p.queries, p.start, p.num_pages, p.kv_len) for p in want_packs)
+    plan = pb.plan_for_batch(b, split_policy=pb.PAT_SPLIT_MEAN)
+    ex = check_schedule(b, plan)
+    want = op.long_kv_split(want_packs, b.kv_lens, b.page_size)
+    assert _canon(_items(ex)) == _canon((p.queries, p.start, p.num_pages, p.kv_len) for p in want)
+    naive = op.naive_packs(op.build_forest(b.block_tables, b.kv_lens, b.page_size), b.kv_lens, b.page_size)
+    plan = pb.plan_for_batch(b, mode=pb.PAT_MODE_NAIVE_PER_NODE, split_policy=pb.PAT_SPLIT_NONE)
+    ex = check_schedule(b, plan)
+    assert _canon(_items(ex)) == _canon((p.queries, p.start, p.num_pages, p.kv_len) for p in naive)
+    # the default (device-aware) plan: invariants only
+    check_schedule(b, pb.plan_for_batch(b))
+
+
 def test_planner_reproduces_hand_worked_example():
     g = json.load(open(os.path.join(ROOT, "tests", "golden", "tree_heuristic_worked_example.json")))
     rows = g["block_tables"]
