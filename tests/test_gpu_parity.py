@@ -221,6 +221,33 @@ def test_batches_of_a_few_rounds_with_short_leaves(case):
          f"tiles={list(st.tile_histogram)[:5]} err={err:.2e} lse_err={lerr:.2e}")
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_trees_under_the_default_plan(seed):
+    # (B, L) trees drawn at random -- one to three shared levels, 24 to 384 requests, node lengths from
+    # one page to thousands of tokens, the paper's head settings, both dtypes, both layouts -- under
+    # the planner's own choices (one round, a few rounds, many rounds, wavefront items), every request
+    # against the oracle
+    rng = np.random.default_rng(4000 + seed)
+    levels = int(rng.integers(1, 4))
+    B = [int(rng.choice([1, 2, 4]))]
+    for _ in range(levels - 1):
+        B.append(B[-1] * int(rng.choice([1, 2, 4])))
+    B.append(B[-1] * int(rng.choice([6, 12, 24])))
+    hi = [int(rng.choice([16, 64, 400, 3000])) for _ in B]
+    L = [(lambda r, n, h=h: r.integers(1, h + 1, n)) for h in hi]
+    hq, hkv = [(64, 8), (32, 8), (16, 8), (32, 32)][seed % 4]
+    dtype, layout = ("bf16", "fp16")[seed % 2], ("NHD", "HND")[(seed // 2) % 2]
+    b = wl.tree_batch(B, L, num_q_heads=hq, num_kv_heads=hkv, dtype=dtype, seed=4000 + seed)
+    _log(f"case random tree seed={seed} B={B} max L={hi} heads={hq}/{hkv} {dtype} {layout} "
+         f"{b.unique_kv_bytes() / 1e6:.1f} MB")
+    tensors = wl.make_tensors(b, device="cuda", poison=True, layout=layout)
+    out, lse, plan = run_hip(b, tensors)
+    st = plan.stats()
+    err, lerr = compare_all_requests_in_groups(b, out, lse, tensors, group=128)
+    _log(f"  items={st.num_items} workgroups={st.num_workgroups} wave_items={st.num_wave_items} "
+         f"tiles={list(st.tile_histogram)[:5]} err={err:.2e} lse_err={lerr:.2e}")
+
+
 def test_wavefront_items_many_per_wavefront():
     # far more items than the 8 x 4 wavefronts of four persistent workgroups: every wavefront walks a
     # list of items, requesting the next item's rows while it finishes the current one
