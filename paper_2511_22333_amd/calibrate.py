@@ -8,6 +8,7 @@ kernel-equivalence run, KV-length decision; sec. "Tile Selection").
     python -m paper_2511_22333_amd.calibrate sweep-kv      # KV-length thresholds of the selector
     python -m paper_2511_22333_amd.calibrate model         # run-time model of the split (default)
     python -m paper_2511_22333_amd.calibrate grid          # (B, L) trees x head settings x modes
+    python -m paper_2511_22333_amd.calibrate timeline C3   # per-workgroup timeline of one forward launch
 
 The run-time model:
 
@@ -290,6 +291,74 @@ def grid(trees=GRID_TREES, heads=GRID_HEADS, modes=GRID_MODES, launches=20, copi
     return rows
 
 
+# ---- per-workgroup timeline of one forward launch (the paper's Fig. 12 on this GPU) ---------------
+def timeline(batch, warm=6, **plan_kw):
+    """One traced forward launch (pat_debug_set_trace) after `warm` untraced steps, on KV pools the
+    launch has not seen.  Returns a dict of numpy arrays per workgroup / wavefront item, in launch order:
+    start, end (us from the first start), tile, kv_len, xcc, cu (a CU's id within the chip), and the
+    four marks (us since the record's start, nan where the tile takes none); plus the plan's stats."""
+    plan = pb.plan_for_batch(batch, **plan_kw)
+    st = plan.stats()
+    dev, ws = pb.alloc_plan_buffers(plan)
+    pb.pat_plan_upload(plan, dev)
+    R = max(2, min(20, (1 << 30) // max(1, batch.unique_kv_bytes())))
+    copies = [wl.make_tensors(batch, seed=i, device="cuda") for i in range(R)]
+    out = torch.empty_like(copies[0][0])
+    lse = torch.empty(batch.num_requests, batch.num_q_heads, dtype=torch.float32, device="cuda")
+    rec = torch.zeros((int(st.num_workgroups) + int(st.num_wave_items) + 8) * 8, dtype=torch.int64, device="cuda")
+    for i in range(warm):
+        q, kp, vp, sd = copies[i % R]
+        pb.pat_decode_attention(plan, q, kp, vp, sd, batch.softmax_scale, out, lse, ws)
+    torch.cuda.synchronize()
+    pb.pat_debug_set_trace(rec)
+    try:
+        q, kp, vp, sd = copies[warm % R]
+        pb.pat_forward(plan, q, kp, vp, sd, batch.softmax_scale, out, lse, ws)
+        torch.cuda.synchronize()
+    finally:
+        pb.pat_debug_set_trace(None)
+    t = rec.cpu().numpy().reshape(-1, 8)
+    t = t[t[:, 0] > 0]
+    t0 = t[:, 0].min()
+    hw = t[:, 2] & 0xFFFFFFFF
+    xcc = (t[:, 2] >> 32) & 0xF
+    marks = np.where(t[:, 4:8] > 0, (t[:, 4:8] - t[:, 0:1]) / 100.0, np.nan)
+    return {"start": (t[:, 0] - t0) / 100.0, "end": (t[:, 1] - t0) / 100.0, "tile": t[:, 3] >> 32,
+            "kv_len": t[:, 3] & 0xFFFFFFFF, "xcc": xcc,
+            "cu": xcc * 1000 + ((hw >> 13) & 7) * 100 + ((hw >> 12) & 1) * 20 + ((hw >> 8) & 0xF),
+            "marks": marks, "stats": st}
+
+
+def timeline_report(name, tl, out=print):
+    start, end, tile = tl["start"], tl["end"], tl["tile"]
+    span = float(end.max())
+    st = tl["stats"]
+    out(f"{name}: {len(start)} records, launch span {span:.1f} us, {int(st.num_workgroups)} workgroups, "
+        f"{int(st.num_wave_items)} wavefront items, tiles {list(st.tile_histogram)[:pb.lib.pat_num_tiles()]}")
+    names = {t: f"tile {t} (m = {m}, n = {n})" for t, m, n in built_tiles()}
+    for tid in np.unique(tile):
+        m = tile == tid
+        d = end[m] - start[m]
+        out(f"  {names.get(int(tid), tid)}: {int(m.sum())} records, kv {int(tl['kv_len'][m].min())}..{int(tl['kv_len'][m].max())}; "
+            f"start {start[m].min():.1f} / {np.median(start[m]):.1f} / {start[m].max():.1f} us (min / median / max); "
+            f"duration {d.min():.1f} / {np.median(d):.1f} / {d.max():.1f}; last end {end[m].max():.1f}")
+        for k, what in enumerate(("mark 0", "mark 1", "mark 2", "mark 3")):
+            v = tl["marks"][m, k]
+            v = v[~np.isnan(v)]
+            if len(v):
+                out(f"      {what} after start: {v.min():.2f} / {np.median(v):.2f} / {v.max():.2f} us")
+    grid_t = np.linspace(0.0, span, 21)
+    out("  records running at 0 %, 5 %, ... 100 % of the span: "
+        + " ".join(str(int(((start <= x) & (end > x)).sum())) for x in grid_t))
+    cus = np.unique(tl["cu"])
+    busy = np.array([(end[tl["cu"] == c] - start[tl["cu"] == c]).sum() for c in cus])
+    last = np.array([end[tl["cu"] == c].max() for c in cus])
+    out(f"  {len(cus)} CUs took work; busy {busy.mean() / span * 100:.0f} % of the span on average "
+        f"(least busy {busy.min() / span * 100:.0f} %); a CU's last end: {last.min():.1f} / {np.median(last):.1f} / {last.max():.1f} us")
+    per_xcc = [float((end[tl["xcc"] == x] - start[tl["xcc"] == x]).sum()) for x in range(8)]
+    out("  busy time per XCD (us): " + " ".join(f"{v:.0f}" for v in per_xcc))
+
+
 def run_model():
     rows = []
     for b in _one_round_batches():
@@ -348,6 +417,10 @@ def main(argv=None):
         print("unshared requests:            kv   n = 128 (4 wavefronts)   n = 32 (1 wavefront)")
         for kv, a, c in leaves:
             print(f"{kv:34d} {a:22.1f} {c:22.1f}   {'n=128' if a < c else 'n=32'}")
+    elif what == "timeline":
+        for name in (argv[1:] or ["C2", "C3", "C4"]):
+            b = wl.config(name) if name in wl.CONFIG_NAMES else wl.extra_config(name)
+            timeline_report(name, timeline(b))
     elif what == "grid":
         names = [n for n, _ in GRID_MODES]
         print("us per step (forward + merge), FP16, head dim 128; speed-up = no-sharing / pat")

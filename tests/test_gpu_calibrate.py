@@ -6,6 +6,7 @@ import pytest
 
 from paper_2511_22333_amd import calibrate
 from paper_2511_22333_amd import binding as pb
+from paper_2511_22333_amd import workloads as wl
 
 from gpu_util import compare, run_oracle
 
@@ -55,3 +56,16 @@ def test_grid_of_trees_gives_one_result_in_every_mode():
         print(f"  {B} {L} {heads}: {us}, modes differ by {dev:.1e}", flush=True)
         assert set(us) == {n for n, _ in calibrate.GRID_MODES} and all(v > 0 for v in us.values())
         assert dev < 4e-3                                       # one attention, four schedules (fp16 output)
+
+
+def test_timeline_of_a_launch_accounts_for_every_workgroup():
+    print("case timeline", flush=True)
+    b = wl.tree_batch([1, 4, 40], [256, 128, lambda rng, n: rng.integers(1, 300, n)], num_q_heads=16, num_kv_heads=4,
+                      dtype="bf16", seed=21)
+    tl = calibrate.timeline(b, warm=2)
+    st = tl["stats"]
+    assert len(tl["start"]) == st.num_workgroups + st.num_wave_items
+    assert (tl["end"] > tl["start"]).all() and tl["end"].max() < 10000.0          # microseconds, one launch
+    hist = np.bincount(tl["tile"].astype(int), minlength=8)
+    calibrate.timeline_report("timeline test", tl, out=lambda line: print("  " + line, flush=True))
+    assert hist.sum() == len(tl["start"]) and len(np.unique(tl["cu"])) <= 256
